@@ -1,0 +1,170 @@
+/*
+ * st_conv.h - C ABI of the fused multi-tenant convolution library for MI355X (gfx950).
+ *
+ * The problem follows the paper's kernel-level experiment (Section 4.1): a set of independent
+ * per-tenant layer problems, each with its own weights and inputs, with all data already resident on
+ * the device, is executed under one of three issue policies (Figure 6):
+ *   space-time : every tenant's problem in ONE launch whose workgroups are divided among tenants
+ *                (the "super-kernel" of Section 4),
+ *   time-only  : one launch per tenant, one after another,
+ *   space-only : one launch per tenant, each on its own stream.
+ * The paper batches same-shape matrix products through a vendor call and names variable-size batching
+ * as the route to different shapes (Section 4.1, last paragraph); here each problem is a convolution
+ * in implicit im2col form (M = N*P*Q output pixels, Ngemm = K filters, Kgemm = C*R*S, the reading
+ * fixed by the worked example of Section 4.1) and shapes may differ per tenant.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers, allocated and owned by the caller, borrowed by the plan
+ *     until it is destroyed or the tenant is rebound.  The library never frees them.
+ *   - Layout: activations NHWC, weights KRSC (filter-major, channel fastest), outputs NHWC (N,P,Q,K).
+ *   - Streams are hipStream_t passed as void*; NULL is the default stream.  Run calls are
+ *     asynchronous, never synchronise and never allocate.
+ *   - Every function returns st_status; on failure no output argument is written (plan pointers are
+ *     left NULL) and st_last_error_message() holds a thread-local description.
+ *   - Same plan + same inputs => bitwise identical outputs on every run and under every issue policy
+ *     (no floating-point atomics; split-K partials are summed in a fixed order).
+ *   - A plan that uses split-K owns a workspace: two runs of the same plan must not overlap in time.
+ */
+#ifndef ST_CONV_H
+#define ST_CONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ST_OK = 0,
+  ST_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, empty output, aliasing, bad index   */
+  ST_ERR_UNSUPPORTED = 2,   /* unknown dtype/layout, tensor with >= 2^31 elements, host-only plan run */
+  ST_ERR_OUT_OF_MEMORY = 3, /* host or device allocation failed                                      */
+  ST_ERR_DEVICE = 4         /* any other HIP error (text in st_last_error_message)                   */
+} st_status;
+
+typedef enum { ST_DT_F32 = 0, ST_DT_BF16 = 1, ST_DT_F16 = 2 } st_dtype;
+typedef enum { ST_LAYOUT_NHWC_KRSC = 0 } st_layout;
+enum { ST_EPI_RELU = 1u, ST_EPI_RESIDUAL = 2u };
+
+/* One tenant's layer.  y[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]
+ * with zeros outside the image, P = floor((H+2*pad-R)/stride)+1 (Q likewise), no bias, dilation 1,
+ * groups 1; products are exact in fp32 and accumulated in fp32.  Epilogue order: + residual (read as
+ * out_dtype, added in fp32), then ReLU, then rounding to out_dtype (nearest, ties to even). */
+typedef struct st_conv_desc {
+  int32_t N, C, H, W;    /* input batch, channels, height, width                         */
+  int32_t K, R, S;       /* filters, filter height, filter width                         */
+  int32_t stride, pad;   /* same in both spatial dimensions                              */
+  int32_t in_dtype;      /* st_dtype of x and w                                          */
+  int32_t out_dtype;     /* ST_DT_F32 or equal to in_dtype                               */
+  int32_t layout;        /* st_layout                                                    */
+  uint32_t epilogue;     /* ST_EPI_* bits                                                */
+  int32_t reserved;      /* must be 0                                                    */
+  const void* x;         /* device, N*H*W*C elements of in_dtype                         */
+  const void* w;         /* device, K*R*S*C elements of in_dtype                         */
+  void* y;               /* device, N*P*Q*K elements of out_dtype, written               */
+  const void* residual;  /* device, same shape and dtype as y; required iff ST_EPI_RESIDUAL */
+} st_conv_desc;
+
+/* Planner knobs; pass NULL for defaults.  Zero-initialise, then set what you need. */
+typedef struct st_plan_opts {
+  int32_t tile_cfg;      /* 0 = choose per tenant; 1 + index into st_tile_shape() to force one       */
+  int32_t split_k;       /* 0 = choose per tenant; >= 1 forces that factor (clamped to the K steps)  */
+  int32_t order;         /* 0 = longest work item first (default); 1 = tenant-major                  */
+  int32_t host_only;     /* 1 = build the tables on the host only (no device calls); run => error    */
+  int32_t target_items;  /* 0 = default; else desired number of work items in the fused launch       */
+  int32_t reserved[3];   /* must be 0                                                                */
+} st_plan_opts;
+
+/* One workgroup's assignment: the bit-exact object of the plan.  tile_m counts pixel tiles (MT rows
+ * of the im2col matrix), tile_n channel tiles (NT filters), k_split_idx which slice of Kgemm. */
+typedef struct st_work_item {
+  uint16_t tenant;
+  uint16_t k_split_idx;
+  uint32_t tile_m;
+  uint32_t tile_n;
+  uint32_t reserved;
+} st_work_item;
+
+typedef struct st_tenant_info {
+  int32_t P, Q;
+  int64_t M, Ngemm, Kgemm;     /* im2col product sizes                                      */
+  int64_t flops;               /* 2*M*Ngemm*Kgemm (padded taps counted)                     */
+  int64_t bytes;               /* x + w + y, each element once                              */
+  int32_t tile_cfg;            /* index into st_tile_shape()                                */
+  int32_t MT, NT;              /* pixels and filters per tile                               */
+  int32_t tiles_m, tiles_n;
+  int32_t split_k;             /* slices of Kgemm per output tile                           */
+  int32_t k_steps;             /* K steps (of st_k_step_bytes() bytes per row) over Kgemm   */
+  int32_t k_steps_per_split;   /* ceil(k_steps / split_k); the last slice may be shorter    */
+  int64_t item_begin;          /* slice [item_begin, item_begin+item_count) of the          */
+  int64_t item_count;          /*   tenant-major work list belongs to this tenant           */
+} st_tenant_info;
+
+typedef struct st_plan_info {
+  int32_t n_tenants;
+  int32_t host_only;
+  int64_t n_items;             /* workgroups in the fused launch                            */
+  int64_t flops, bytes;        /* sums over tenants                                         */
+  int64_t workspace_bytes;     /* split-K partials + counters owned by the plan             */
+} st_plan_info;
+
+typedef struct st_plan st_plan; /* opaque */
+
+/* Section 4 ("the scheduler must dynamically schedule kernels as they arrive"): build the launch
+ * plan for whatever set of problems is ready.  Validates every descriptor, derives P, Q and the
+ * im2col sizes, picks a tile shape and a split-K factor per tenant so that the launch fills the
+ * 256 compute units, enumerates the work items, and uploads the tenant table and work lists.
+ * n_tenants == 0 gives an empty plan whose runs are no-ops.  Host allocations and (unless
+ * opts->host_only) device allocations happen here and only here. */
+st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, const st_plan_opts* opts,
+                       st_plan** out_plan);
+
+/* Space-time policy (Section 4, Figure 6): one launch, grid = number of work items. */
+st_status st_conv_run(const st_plan* plan, void* hip_stream);
+
+/* Time-only policy (Section 3, Figure 6): one launch per tenant on one in-order stream, no host
+ * synchronisation in between.  Same kernel, same tiles, same work items as st_conv_run. */
+st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream);
+
+/* Space-only policy (Section 3 "explicit spatial multiplexing", Figure 6): tenant t is launched on
+ * hip_streams[t % n_streams].  hip_streams[0] is the anchor: every other stream first waits for the
+ * work already queued on it, and on return it waits for every other stream, so work queued on
+ * hip_streams[0] afterwards (e.g. a timing event) follows all tenants. */
+st_status st_conv_run_space_only(const st_plan* plan, void* const* hip_streams, int32_t n_streams);
+
+/* Replace tenant pointers (the cached-plan path of Section 4: same shapes, new inputs).  NULL keeps
+ * the current pointer.  Synchronous small upload on the default stream; not for use while a run of
+ * this plan is in flight. */
+st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const void* x, const void* w, void* y,
+                              const void* residual);
+
+/* Introspection (used by the bit-exact work-list tests and by reports). */
+st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out);
+st_status st_conv_plan_tenant_info(const st_plan* plan, int32_t tenant, st_tenant_info* out);
+/* Host copies of the work lists, valid until the plan is destroyed.  which: 0 = order used by the
+ * fused launch, 1 = tenant-major order used by the two baselines. */
+st_status st_conv_plan_worklist(const st_plan* plan, int32_t which, const st_work_item** items,
+                                int64_t* n_items);
+void st_conv_plan_destroy(st_plan* plan);
+
+/* Tile family: shape of config `index` (pixels x filters); returns ST_ERR_INVALID_ARG past the end. */
+st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT);
+int32_t st_tile_count(void);
+int32_t st_k_step_bytes(void);
+
+/* 3x3 / stride 2 / pad 1 style max-pool on an NHWC tensor, the one non-convolution step between the
+ * stem and the first bottleneck of a ResNet-50-shaped stack.  x: N*H*W*C, y: N*P*Q*C elements of
+ * `dtype`, device pointers; padding never wins the maximum.  Asynchronous on hip_stream. */
+st_status st_maxpool_nhwc(const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C,
+                          int32_t win, int32_t stride, int32_t pad, int32_t dtype, void* hip_stream);
+
+/* Launches an empty kernel: measures the launch floor the fused policy pays once. */
+st_status st_launch_empty(void* hip_stream);
+
+const char* st_status_string(st_status s);
+const char* st_last_error_message(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ST_CONV_H */

@@ -1,0 +1,447 @@
+// Host side of the library: descriptor validation, derived sizes, tile / split-K selection, work-list
+// construction, device tables, the three issue policies and the C ABI (declared in st_conv.h).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "st_internal.h"
+
+using namespace st;
+
+// ---------------------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static st_status fail(st_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+static st_status hip_fail(hipError_t e, const char* what) {
+  return fail(e == hipErrorOutOfMemory ? ST_ERR_OUT_OF_MEMORY : ST_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+#define ST_HIP(call)                                   \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) return hip_fail(e_, #call);  \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------------------
+// plan object
+// ---------------------------------------------------------------------------------------------------
+struct st_plan {
+  std::vector<st_conv_desc> descs;
+  std::vector<st_tenant_info> info;
+  std::vector<TenantDev> tenants;           // host mirror of the device table
+  std::vector<st_work_item> items_fused;    // order of the fused launch
+  std::vector<st_work_item> items_tenant;   // tenant-major, sliced by the baselines
+  bool host_only = false;
+  int64_t flops = 0, bytes = 0, workspace_bytes = 0;
+  // device
+  TenantDev* d_tenants = nullptr;
+  st_work_item* d_items_fused = nullptr;
+  st_work_item* d_items_tenant = nullptr;
+  char* d_workspace = nullptr;              // all tenants' split-K partials, then all counters
+  hipEvent_t ev_fork = nullptr;
+  std::vector<hipEvent_t> ev_join;          // one per stream slot used by space-only
+};
+
+static int elem_size(int dt) { return dt == ST_DT_F32 ? 4 : 2; }
+
+static st_status validate(const st_conv_desc& d, int t) {
+  if (d.N <= 0 || d.C <= 0 || d.H <= 0 || d.W <= 0 || d.K <= 0 || d.R <= 0 || d.S <= 0)
+    return fail(ST_ERR_INVALID_ARG, "tenant %d: every size must be positive", t);
+  if (d.stride <= 0 || d.pad < 0) return fail(ST_ERR_INVALID_ARG, "tenant %d: stride must be > 0 and pad >= 0", t);
+  if (d.reserved != 0) return fail(ST_ERR_INVALID_ARG, "tenant %d: reserved field must be 0", t);
+  if (d.in_dtype != ST_DT_F32 && d.in_dtype != ST_DT_BF16 && d.in_dtype != ST_DT_F16)
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown in_dtype %d", t, d.in_dtype);
+  if (d.out_dtype != ST_DT_F32 && d.out_dtype != d.in_dtype)
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: out_dtype must be f32 or equal to in_dtype", t);
+  if (d.layout != ST_LAYOUT_NHWC_KRSC) return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown layout %d", t, d.layout);
+  if (d.epilogue & ~(uint32_t)(ST_EPI_RELU | ST_EPI_RESIDUAL))
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown epilogue bits 0x%x", t, d.epilogue);
+  if ((int64_t)d.H + 2 * (int64_t)d.pad < d.R || (int64_t)d.W + 2 * (int64_t)d.pad < d.S)
+    return fail(ST_ERR_INVALID_ARG, "tenant %d: filter larger than the padded image (empty output)", t);
+  if (!d.x || !d.w || !d.y) return fail(ST_ERR_INVALID_ARG, "tenant %d: x, w and y must be non-NULL", t);
+  if ((d.epilogue & ST_EPI_RESIDUAL) && !d.residual)
+    return fail(ST_ERR_INVALID_ARG, "tenant %d: ST_EPI_RESIDUAL without a residual pointer", t);
+  if ((const void*)d.y == d.x || (const void*)d.y == d.w)
+    return fail(ST_ERR_INVALID_ARG, "tenant %d: y must not alias x or w", t);
+  const int64_t lim = (int64_t)1 << 31;
+  const int64_t P = ((int64_t)d.H + 2 * d.pad - d.R) / d.stride + 1, Q = ((int64_t)d.W + 2 * d.pad - d.S) / d.stride + 1;
+  const int64_t nx = (int64_t)d.N * d.C * d.H * d.W, nw = (int64_t)d.K * d.C * d.R * d.S, ny = (int64_t)d.N * P * Q * d.K;
+  if (nx >= lim || nw >= lim || ny >= lim || (int64_t)d.pad >= (1 << 20) || (int64_t)d.stride >= (1 << 20))
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: tensors of 2^31 or more elements are not supported", t);
+  return ST_OK;
+}
+
+static int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// Tile shape and split-K factor for one tenant.  `want` is the number of work items this tenant should
+// contribute so that the whole launch covers the compute units a few times over, in proportion to the
+// tenant's share of the arithmetic.
+static void choose_tile(int64_t M, int64_t Ng, int k_steps, int64_t want, const st_plan_opts& o, int* cfg_out,
+                        int* split_out) {
+  const int min_steps_per_split = 4;
+  const int max_split = std::max(1, std::min(k_steps / min_steps_per_split, 256));
+  int cfg = -1;
+  if (o.tile_cfg > 0) {
+    cfg = o.tile_cfg - 1;
+  } else {
+    double eff[kNumTileCfgs], best_eff = 0.0;
+    int64_t tiles[kNumTileCfgs];
+    for (int c = 0; c < kNumTileCfgs; ++c) {
+      const int64_t tm = cdiv(M, kTileShapes[c].MT), tn = cdiv(Ng, kTileShapes[c].NT);
+      tiles[c] = tm * tn;
+      eff[c] = (double)(M * Ng) / (double)(tm * kTileShapes[c].MT * tn * kTileShapes[c].NT);
+      best_eff = std::max(best_eff, eff[c]);
+    }
+    // largest tile that still yields enough items without split-K
+    for (int c = 0; c < kNumTileCfgs && cfg < 0; ++c)
+      if (eff[c] >= 0.75 * best_eff && tiles[c] >= want) cfg = c;
+    // otherwise the largest tile that reaches the target with split-K; failing that, the one that gets closest
+    if (cfg < 0) {
+      int64_t best_reach = -1;
+      for (int c = 0; c < kNumTileCfgs; ++c) {
+        if (eff[c] < 0.75 * best_eff) continue;
+        const int64_t reach = std::min<int64_t>(want, tiles[c] * max_split);
+        if (reach > best_reach) { best_reach = reach; cfg = c; }
+      }
+    }
+  }
+  const int64_t tiles = (int64_t)cdiv(M, kTileShapes[cfg].MT) * cdiv(Ng, kTileShapes[cfg].NT);
+  int split = 1;
+  if (o.split_k >= 1) split = o.split_k;
+  else if (tiles < want) split = (int)std::min<int64_t>(max_split, (want + tiles - 1) / tiles);
+  split = std::max(1, std::min(split, std::min(k_steps, 65535)));
+  // normalise so that no slice is empty
+  const int per = cdiv(k_steps, split);
+  split = cdiv(k_steps, per);
+  *cfg_out = cfg;
+  *split_out = split;
+}
+
+static void destroy_device(st_plan* p) {
+  if (p->d_tenants) (void)hipFree(p->d_tenants);
+  if (p->d_items_fused) (void)hipFree(p->d_items_fused);
+  if (p->d_items_tenant) (void)hipFree(p->d_items_tenant);
+  if (p->d_workspace) (void)hipFree(p->d_workspace);
+  if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+  for (hipEvent_t e : p->ev_join)
+    if (e) (void)hipEventDestroy(e);
+  p->d_tenants = nullptr;
+  p->d_items_fused = p->d_items_tenant = nullptr;
+  p->d_workspace = nullptr;
+  p->ev_fork = nullptr;
+  p->ev_join.clear();
+}
+
+static st_status upload(st_plan* p) {
+  const size_t n = p->tenants.size();
+  if (n == 0) return ST_OK;
+  // workspace: partial tiles of every split-K tenant, then the counters
+  size_t ws_floats = 0, counters = 0;
+  for (size_t t = 0; t < n; ++t) {
+    const st_tenant_info& ti = p->info[t];
+    if (ti.split_k > 1) {
+      ws_floats += (size_t)ti.tiles_m * ti.tiles_n * ti.split_k * ti.MT * ti.NT;
+      counters += (size_t)ti.tiles_m * ti.tiles_n;
+    }
+  }
+  p->workspace_bytes = (int64_t)(ws_floats * 4 + counters * 4);
+  if (p->host_only) return ST_OK;
+  if (p->workspace_bytes > 0) {
+    ST_HIP(hipMalloc((void**)&p->d_workspace, (size_t)p->workspace_bytes));
+    ST_HIP(hipMemset(p->d_workspace + ws_floats * 4, 0, counters * 4));
+    size_t wf = 0, ct = 0;
+    for (size_t t = 0; t < n; ++t) {
+      const st_tenant_info& ti = p->info[t];
+      if (ti.split_k > 1) {
+        p->tenants[t].ws = (float*)p->d_workspace + wf;
+        p->tenants[t].counters = (uint32_t*)(p->d_workspace + ws_floats * 4) + ct;
+        wf += (size_t)ti.tiles_m * ti.tiles_n * ti.split_k * ti.MT * ti.NT;
+        ct += (size_t)ti.tiles_m * ti.tiles_n;
+      }
+    }
+  }
+  ST_HIP(hipMalloc((void**)&p->d_tenants, n * sizeof(TenantDev)));
+  ST_HIP(hipMemcpy(p->d_tenants, p->tenants.data(), n * sizeof(TenantDev), hipMemcpyHostToDevice));
+  const size_t ib = p->items_fused.size() * sizeof(st_work_item);
+  ST_HIP(hipMalloc((void**)&p->d_items_fused, ib));
+  ST_HIP(hipMalloc((void**)&p->d_items_tenant, ib));
+  ST_HIP(hipMemcpy(p->d_items_fused, p->items_fused.data(), ib, hipMemcpyHostToDevice));
+  ST_HIP(hipMemcpy(p->d_items_tenant, p->items_tenant.data(), ib, hipMemcpyHostToDevice));
+  ST_HIP(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+  p->ev_join.assign(n, nullptr);
+  for (size_t t = 0; t < n; ++t) ST_HIP(hipEventCreateWithFlags(&p->ev_join[t], hipEventDisableTiming));
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, const st_plan_opts* opts,
+                                  st_plan** out_plan) {
+  if (!out_plan) return fail(ST_ERR_INVALID_ARG, "out_plan is NULL");
+  *out_plan = nullptr;
+  if (n_tenants < 0) return fail(ST_ERR_INVALID_ARG, "n_tenants is negative");
+  if (n_tenants > 0 && !descs) return fail(ST_ERR_INVALID_ARG, "descs is NULL");
+  if (n_tenants > 65535) return fail(ST_ERR_UNSUPPORTED, "at most 65535 tenants per plan");
+  st_plan_opts o;
+  std::memset(&o, 0, sizeof(o));
+  if (opts) o = *opts;
+  if (o.tile_cfg < 0 || o.tile_cfg > kNumTileCfgs) return fail(ST_ERR_INVALID_ARG, "opts.tile_cfg out of range");
+  if (o.split_k < 0 || o.order < 0 || o.order > 1 || o.target_items < 0)
+    return fail(ST_ERR_INVALID_ARG, "opts: negative or unknown value");
+  for (int t = 0; t < n_tenants; ++t) {
+    st_status s = validate(descs[t], t);
+    if (s != ST_OK) return s;
+  }
+  st_plan* p = new (std::nothrow) st_plan();
+  if (!p) return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  try {
+    p->host_only = o.host_only != 0;
+    p->descs.assign(descs, descs + n_tenants);
+    p->info.resize(n_tenants);
+    p->tenants.resize(n_tenants);
+    // derived sizes
+    for (int t = 0; t < n_tenants; ++t) {
+      const st_conv_desc& d = descs[t];
+      st_tenant_info& ti = p->info[t];
+      std::memset(&ti, 0, sizeof(ti));
+      ti.P = (d.H + 2 * d.pad - d.R) / d.stride + 1;
+      ti.Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
+      ti.M = (int64_t)d.N * ti.P * ti.Q;
+      ti.Ngemm = d.K;
+      ti.Kgemm = (int64_t)d.C * d.R * d.S;
+      ti.flops = 2 * ti.M * ti.Ngemm * ti.Kgemm;
+      ti.bytes = ((int64_t)d.N * d.C * d.H * d.W + ti.Ngemm * ti.Kgemm) * elem_size(d.in_dtype) +
+                 ti.M * ti.Ngemm * elem_size(d.out_dtype);
+      ti.k_steps = cdiv(ti.Kgemm * elem_size(d.in_dtype), kKStepBytes);
+      p->flops += ti.flops;
+      p->bytes += ti.bytes;
+    }
+    // tile shape and split-K per tenant, in proportion to each tenant's share of the arithmetic
+    const int64_t target = o.target_items > 0 ? o.target_items : 4 * kNumCUs;
+    int64_t fused_total = 0;
+    for (int t = 0; t < n_tenants; ++t) {
+      st_tenant_info& ti = p->info[t];
+      const int64_t want = std::max<int64_t>(1, (int64_t)std::llround((double)target * (double)ti.flops / (double)p->flops));
+      int cfg, split;
+      choose_tile(ti.M, ti.Ngemm, ti.k_steps, want, o, &cfg, &split);
+      ti.tile_cfg = cfg;
+      ti.MT = kTileShapes[cfg].MT;
+      ti.NT = kTileShapes[cfg].NT;
+      ti.tiles_m = cdiv(ti.M, ti.MT);
+      ti.tiles_n = cdiv(ti.Ngemm, ti.NT);
+      ti.split_k = split;
+      ti.k_steps_per_split = cdiv(ti.k_steps, split);
+      ti.item_begin = fused_total;
+      ti.item_count = (int64_t)ti.tiles_m * ti.tiles_n * split;
+      fused_total += ti.item_count;
+    }
+    if (fused_total >= ((int64_t)1 << 31)) {
+      delete p;
+      return fail(ST_ERR_UNSUPPORTED, "more than 2^31 work items");
+    }
+    // tenant-major work list: tenant, pixel tile, filter tile, K slice
+    p->items_tenant.reserve((size_t)fused_total);
+    for (int t = 0; t < n_tenants; ++t) {
+      const st_tenant_info& ti = p->info[t];
+      for (int tm = 0; tm < ti.tiles_m; ++tm)
+        for (int tn = 0; tn < ti.tiles_n; ++tn)
+          for (int s = 0; s < ti.split_k; ++s) {
+            st_work_item it;
+            it.tenant = (uint16_t)t;
+            it.k_split_idx = (uint16_t)s;
+            it.tile_m = (uint32_t)tm;
+            it.tile_n = (uint32_t)tn;
+            it.reserved = 0;
+            p->items_tenant.push_back(it);
+          }
+    }
+    // fused order: longest work item first, so that short items fill the tail of the launch
+    p->items_fused = p->items_tenant;
+    if (o.order == 0) {
+      auto cost = [&](const st_work_item& it) {
+        const st_tenant_info& ti = p->info[it.tenant];
+        const int begin = (int)it.k_split_idx * ti.k_steps_per_split;
+        const int steps = std::min(ti.k_steps, begin + ti.k_steps_per_split) - begin;
+        return (int64_t)steps * ti.MT * ti.NT;
+      };
+      std::stable_sort(p->items_fused.begin(), p->items_fused.end(),
+                       [&](const st_work_item& a, const st_work_item& b) { return cost(a) > cost(b); });
+    }
+    // device records
+    for (int t = 0; t < n_tenants; ++t) {
+      const st_conv_desc& d = descs[t];
+      const st_tenant_info& ti = p->info[t];
+      TenantDev& T = p->tenants[t];
+      std::memset(&T, 0, sizeof(T));
+      T.x = d.x; T.w = d.w; T.y = d.y; T.res = d.residual;
+      T.C = d.C; T.H = d.H; T.W = d.W; T.K = d.K; T.R = d.R; T.S = d.S; T.stride = d.stride; T.pad = d.pad;
+      T.P = ti.P; T.Q = ti.Q; T.PQ = ti.P * ti.Q; T.M = (int32_t)ti.M; T.Kg = (int32_t)ti.Kgemm;
+      T.in_dtype = d.in_dtype; T.out_dtype = d.out_dtype; T.epilogue = (int32_t)d.epilogue;
+      T.cfg = ti.tile_cfg; T.split_k = ti.split_k; T.k_steps = ti.k_steps; T.k_steps_per_split = ti.k_steps_per_split;
+      T.tiles_m = ti.tiles_m; T.tiles_n = ti.tiles_n;
+      T.vec_ok = (d.C % (16 / elem_size(d.in_dtype)) == 0) ? 1 : 0;
+    }
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  st_status s = upload(p);
+  if (s != ST_OK) {
+    destroy_device(p);
+    delete p;
+    return s;
+  }
+  *out_plan = p;
+  return ST_OK;
+}
+
+static st_status check_runnable(const st_plan* plan) {
+  if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->host_only) return fail(ST_ERR_UNSUPPORTED, "plan was built host-only and cannot run");
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run(const st_plan* plan, void* hip_stream) {
+  st_status s = check_runnable(plan);
+  if (s != ST_OK) return s;
+  if (plan->items_fused.empty()) return ST_OK;
+  ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), hip_stream));
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream) {
+  st_status s = check_runnable(plan);
+  if (s != ST_OK) return s;
+  for (size_t t = 0; t < plan->info.size(); ++t) {
+    const st_tenant_info& ti = plan->info[t];
+    ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_tenant + ti.item_begin, ti.item_count, hip_stream));
+  }
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run_space_only(const st_plan* plan, void* const* hip_streams, int32_t n_streams) {
+  st_status s = check_runnable(plan);
+  if (s != ST_OK) return s;
+  if (!hip_streams || n_streams <= 0) return fail(ST_ERR_INVALID_ARG, "need at least one stream");
+  const size_t n = plan->info.size();
+  if (n == 0) return ST_OK;
+  hipStream_t anchor = (hipStream_t)hip_streams[0];
+  const size_t used = std::min<size_t>(n, (size_t)n_streams);
+  if (used > 1) {
+    ST_HIP(hipEventRecord(plan->ev_fork, anchor));
+    for (size_t i = 1; i < used; ++i) ST_HIP(hipStreamWaitEvent((hipStream_t)hip_streams[i], plan->ev_fork, 0));
+  }
+  for (size_t t = 0; t < n; ++t) {
+    const st_tenant_info& ti = plan->info[t];
+    ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_tenant + ti.item_begin, ti.item_count,
+                                   hip_streams[t % (size_t)n_streams]));
+  }
+  for (size_t i = 1; i < used; ++i) {
+    ST_HIP(hipEventRecord(plan->ev_join[i], (hipStream_t)hip_streams[i]));
+    ST_HIP(hipStreamWaitEvent(anchor, plan->ev_join[i], 0));
+  }
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const void* x, const void* w, void* y,
+                                         const void* residual) {
+  if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");
+  if (tenant < 0 || (size_t)tenant >= plan->tenants.size()) return fail(ST_ERR_INVALID_ARG, "tenant index out of range");
+  TenantDev T = plan->tenants[tenant];
+  if (x) T.x = x;
+  if (w) T.w = w;
+  if (y) T.y = y;
+  if (residual) T.res = residual;
+  if (T.y == T.x || T.y == T.w) return fail(ST_ERR_INVALID_ARG, "y must not alias x or w");
+  if (!plan->host_only)
+    ST_HIP(hipMemcpy(plan->d_tenants + tenant, &T, sizeof(T), hipMemcpyHostToDevice));
+  plan->tenants[tenant] = T;
+  st_conv_desc& d = plan->descs[tenant];
+  d.x = T.x; d.w = T.w; d.y = T.y; d.residual = T.res;
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out) {
+  if (!plan || !out) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  out->n_tenants = (int32_t)plan->info.size();
+  out->host_only = plan->host_only ? 1 : 0;
+  out->n_items = (int64_t)plan->items_fused.size();
+  out->flops = plan->flops;
+  out->bytes = plan->bytes;
+  out->workspace_bytes = plan->workspace_bytes;
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_plan_tenant_info(const st_plan* plan, int32_t tenant, st_tenant_info* out) {
+  if (!plan || !out) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  if (tenant < 0 || (size_t)tenant >= plan->info.size()) return fail(ST_ERR_INVALID_ARG, "tenant index out of range");
+  *out = plan->info[tenant];
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_plan_worklist(const st_plan* plan, int32_t which, const st_work_item** items,
+                                           int64_t* n_items) {
+  if (!plan || !items || !n_items) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  if (which != 0 && which != 1) return fail(ST_ERR_INVALID_ARG, "which must be 0 or 1");
+  const std::vector<st_work_item>& v = which == 0 ? plan->items_fused : plan->items_tenant;
+  *items = v.data();
+  *n_items = (int64_t)v.size();
+  return ST_OK;
+}
+
+extern "C" void st_conv_plan_destroy(st_plan* plan) {
+  if (!plan) return;
+  destroy_device(plan);
+  delete plan;
+}
+
+extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT) {
+  if (index < 0 || index >= kNumTileCfgs || !MT || !NT) return fail(ST_ERR_INVALID_ARG, "tile index out of range");
+  *MT = kTileShapes[index].MT;
+  *NT = kTileShapes[index].NT;
+  return ST_OK;
+}
+extern "C" int32_t st_tile_count(void) { return kNumTileCfgs; }
+extern "C" int32_t st_k_step_bytes(void) { return kKStepBytes; }
+
+extern "C" st_status st_maxpool_nhwc(const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t win,
+                                     int32_t stride, int32_t pad, int32_t dtype, void* hip_stream) {
+  if (!x || !y) return fail(ST_ERR_INVALID_ARG, "x and y must be non-NULL");
+  if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || win <= 0 || stride <= 0 || pad < 0)
+    return fail(ST_ERR_INVALID_ARG, "sizes must be positive");
+  if (pad >= win) return fail(ST_ERR_INVALID_ARG, "pad must be smaller than the window");
+  if (H + 2 * pad < win || W + 2 * pad < win) return fail(ST_ERR_INVALID_ARG, "window larger than the padded image");
+  if (dtype != ST_DT_F32 && dtype != ST_DT_BF16 && dtype != ST_DT_F16) return fail(ST_ERR_UNSUPPORTED, "unknown dtype");
+  const int P = (H + 2 * pad - win) / stride + 1, Q = (W + 2 * pad - win) / stride + 1;
+  if ((int64_t)N * H * W * C >= ((int64_t)1 << 31)) return fail(ST_ERR_UNSUPPORTED, "tensor too large");
+  ST_HIP((hipError_t)launch_maxpool(x, y, N, H, W, C, P, Q, win, stride, pad, dtype, hip_stream));
+  return ST_OK;
+}
+
+extern "C" st_status st_launch_empty(void* hip_stream) {
+  ST_HIP((hipError_t)launch_empty(hip_stream));
+  return ST_OK;
+}
+
+extern "C" const char* st_status_string(st_status s) {
+  switch (s) {
+    case ST_OK: return "ST_OK";
+    case ST_ERR_INVALID_ARG: return "ST_ERR_INVALID_ARG";
+    case ST_ERR_UNSUPPORTED: return "ST_ERR_UNSUPPORTED";
+    case ST_ERR_OUT_OF_MEMORY: return "ST_ERR_OUT_OF_MEMORY";
+    case ST_ERR_DEVICE: return "ST_ERR_DEVICE";
+  }
+  return "ST_ERR_UNKNOWN";
+}
+extern "C" const char* st_last_error_message(void) { return g_err; }

@@ -1,0 +1,240 @@
+"""Thin ctypes binding of libst_conv.so: same names as the C ABI (include/st_conv.h), argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; there is no fallback:
+if the shared library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libst_conv.so")
+
+ST_OK, ST_ERR_INVALID_ARG, ST_ERR_UNSUPPORTED, ST_ERR_OUT_OF_MEMORY, ST_ERR_DEVICE = range(5)
+ST_DT_F32, ST_DT_BF16, ST_DT_F16 = 0, 1, 2
+ST_LAYOUT_NHWC_KRSC = 0
+ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
+DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
+
+EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only",
+           "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
+           "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_k_step_bytes", "st_maxpool_nhwc",
+           "st_launch_empty", "st_status_string", "st_last_error_message"]
+
+
+class st_conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad",
+                                              "in_dtype", "out_dtype", "layout")] + \
+               [("epilogue", ctypes.c_uint32), ("reserved", ctypes.c_int32),
+                ("x", ctypes.c_void_p), ("w", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("residual", ctypes.c_void_p)]
+
+
+class st_plan_opts(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("tile_cfg", "split_k", "order", "host_only", "target_items")] + \
+               [("reserved", ctypes.c_int32 * 3)]
+
+
+class st_work_item(ctypes.Structure):
+    _fields_ = [("tenant", ctypes.c_uint16), ("k_split_idx", ctypes.c_uint16), ("tile_m", ctypes.c_uint32),
+                ("tile_n", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+WORK_ITEM_DTYPE = np.dtype([("tenant", "<u2"), ("k_split_idx", "<u2"), ("tile_m", "<u4"), ("tile_n", "<u4"),
+                            ("reserved", "<u4")])
+
+
+class st_tenant_info(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("M", ctypes.c_int64), ("Ngemm", ctypes.c_int64),
+                ("Kgemm", ctypes.c_int64), ("flops", ctypes.c_int64), ("bytes", ctypes.c_int64),
+                ("tile_cfg", ctypes.c_int32), ("MT", ctypes.c_int32), ("NT", ctypes.c_int32),
+                ("tiles_m", ctypes.c_int32), ("tiles_n", ctypes.c_int32), ("split_k", ctypes.c_int32),
+                ("k_steps", ctypes.c_int32), ("k_steps_per_split", ctypes.c_int32),
+                ("item_begin", ctypes.c_int64), ("item_count", ctypes.c_int64)]
+
+
+class st_plan_info(ctypes.Structure):
+    _fields_ = [("n_tenants", ctypes.c_int32), ("host_only", ctypes.c_int32), ("n_items", ctypes.c_int64),
+                ("flops", ctypes.c_int64), ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+
+
+class StError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().st_last_error_message().decode()
+        super().__init__(f"{where}: {lib().st_status_string(status).decode()}: {msg}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it was never built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1901_00041_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        P = ctypes.POINTER
+        L.st_conv_plan.argtypes = [P(st_conv_desc), i32, P(st_plan_opts), P(vp)]
+        L.st_conv_run.argtypes = [vp, vp]
+        L.st_conv_run_time_only.argtypes = [vp, vp]
+        L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
+        L.st_conv_plan_rebind.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.st_conv_plan_info.argtypes = [vp, P(st_plan_info)]
+        L.st_conv_plan_tenant_info.argtypes = [vp, i32, P(st_tenant_info)]
+        L.st_conv_plan_worklist.argtypes = [vp, i32, P(P(st_work_item)), P(i64)]
+        L.st_conv_plan_destroy.argtypes = [vp]
+        L.st_conv_plan_destroy.restype = None
+        L.st_tile_shape.argtypes = [i32, P(i32), P(i32)]
+        L.st_tile_count.argtypes = []
+        L.st_k_step_bytes.argtypes = []
+        L.st_maxpool_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
+        L.st_launch_empty.argtypes = [vp]
+        L.st_status_string.argtypes = [i32]
+        L.st_status_string.restype = ctypes.c_char_p
+        L.st_last_error_message.argtypes = []
+        L.st_last_error_message.restype = ctypes.c_char_p
+        for name in ("st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only",
+                     "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info",
+                     "st_conv_plan_worklist", "st_tile_shape", "st_tile_count", "st_k_step_bytes",
+                     "st_maxpool_nhwc", "st_launch_empty"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor, or an integer address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return int(s.cuda_stream)
+
+
+def make_desc(N, C, H, W, K, R, S, stride, pad, in_dtype, out_dtype, x, w, y, residual=None,
+              epilogue=0, layout=ST_LAYOUT_NHWC_KRSC) -> st_conv_desc:
+    d = st_conv_desc()
+    d.N, d.C, d.H, d.W, d.K, d.R, d.S, d.stride, d.pad = N, C, H, W, K, R, S, stride, pad
+    d.in_dtype = DTYPE_CODE.get(in_dtype, in_dtype)
+    d.out_dtype = DTYPE_CODE.get(out_dtype, out_dtype)
+    d.layout, d.epilogue, d.reserved = layout, epilogue, 0
+    d.x, d.w, d.y, d.residual = _ptr(x), _ptr(w), _ptr(y), _ptr(residual)
+    return d
+
+
+class Plan:
+    """Owns an st_plan*; keeps the tensors it borrows alive."""
+
+    def __init__(self, handle: int, keep):
+        self.handle = handle
+        self._keep = keep
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "handle", None):
+            lib().st_conv_plan_destroy(self.handle)
+            self.handle = None
+
+
+def st_conv_plan(descs: Sequence[st_conv_desc], opts: Optional[st_plan_opts] = None, keep=None) -> Plan:
+    n = len(descs)
+    arr = (st_conv_desc * max(n, 1))(*descs)
+    out = ctypes.c_void_p()
+    st = lib().st_conv_plan(arr, n, ctypes.byref(opts) if opts is not None else None, ctypes.byref(out))
+    if st != ST_OK:
+        raise StError(st, "st_conv_plan")
+    return Plan(out.value, keep)
+
+
+def plan_opts(tile_cfg=0, split_k=0, order=0, host_only=0, target_items=0) -> st_plan_opts:
+    o = st_plan_opts()
+    o.tile_cfg, o.split_k, o.order, o.host_only, o.target_items = tile_cfg, split_k, order, host_only, target_items
+    return o
+
+
+def _check(st, where):
+    if st != ST_OK:
+        raise StError(st, where)
+
+
+def st_conv_run(plan: Plan, stream=None) -> None:
+    _check(lib().st_conv_run(plan.handle, _stream(stream)), "st_conv_run")
+
+
+def st_conv_run_time_only(plan: Plan, stream=None) -> None:
+    _check(lib().st_conv_run_time_only(plan.handle, _stream(stream)), "st_conv_run_time_only")
+
+
+def st_conv_run_space_only(plan: Plan, streams) -> None:
+    hs = [_stream(s) for s in streams]
+    arr = (ctypes.c_void_p * max(len(hs), 1))(*hs)
+    _check(lib().st_conv_run_space_only(plan.handle, arr, len(hs)), "st_conv_run_space_only")
+
+
+def st_conv_plan_rebind(plan: Plan, tenant: int, x=None, w=None, y=None, residual=None) -> None:
+    _check(lib().st_conv_plan_rebind(plan.handle, tenant, _ptr(x), _ptr(w), _ptr(y), _ptr(residual)),
+           "st_conv_plan_rebind")
+    if plan._keep is not None:
+        plan._keep.append((x, w, y, residual))
+
+
+def st_conv_plan_info(plan: Plan) -> st_plan_info:
+    out = st_plan_info()
+    _check(lib().st_conv_plan_info(plan.handle, ctypes.byref(out)), "st_conv_plan_info")
+    return out
+
+
+def st_conv_plan_tenant_info(plan: Plan, tenant: int) -> st_tenant_info:
+    out = st_tenant_info()
+    _check(lib().st_conv_plan_tenant_info(plan.handle, tenant, ctypes.byref(out)), "st_conv_plan_tenant_info")
+    return out
+
+
+def st_conv_plan_worklist(plan: Plan, which: int = 0) -> np.ndarray:
+    """Copy of a work list as a structured array (fields as in st_work_item)."""
+    p = ctypes.POINTER(st_work_item)()
+    n = ctypes.c_int64()
+    _check(lib().st_conv_plan_worklist(plan.handle, which, ctypes.byref(p), ctypes.byref(n)), "st_conv_plan_worklist")
+    if n.value == 0:
+        return np.zeros(0, dtype=WORK_ITEM_DTYPE)
+    buf = ctypes.string_at(p, n.value * ctypes.sizeof(st_work_item))
+    return np.frombuffer(buf, dtype=WORK_ITEM_DTYPE).copy()
+
+
+def st_tile_shape(index: int):
+    mt, nt = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().st_tile_shape(index, ctypes.byref(mt), ctypes.byref(nt)), "st_tile_shape")
+    return mt.value, nt.value
+
+
+def st_tile_count() -> int:
+    return lib().st_tile_count()
+
+
+def st_k_step_bytes() -> int:
+    return lib().st_k_step_bytes()
+
+
+def st_maxpool_nhwc(x, y, N, H, W, C, win, stride, pad, dtype, stream=None) -> None:
+    _check(lib().st_maxpool_nhwc(_ptr(x), _ptr(y), N, H, W, C, win, stride, pad, DTYPE_CODE.get(dtype, dtype),
+                                 _stream(stream)), "st_maxpool_nhwc")
+
+
+def st_launch_empty(stream=None) -> None:
+    _check(lib().st_launch_empty(_stream(stream)), "st_launch_empty")

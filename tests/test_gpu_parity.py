@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from paper_1901_00041_amd import st_conv as sc
+from paper_1901_00041_amd import synth
+from paper_1901_00041_amd.synth import ConvShape
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    sc.lib()   # fails loudly when the HIP library was not built
+    return torch
+
+
+def _sync(torch):
+    torch.cuda.synchronize()
+
+
+# several tiles plus ragged tails in M (198 pixels), N (40 filters) and K (144, 400, 147 ...)
+SMALL = [
+    ConvShape(2, 16, 9, 11, 40, 3, 3, 1, 1, "bf16", "f32"),
+    ConvShape(1, 32, 12, 10, 72, 3, 3, 2, 1, "bf16", "f32"),
+    ConvShape(3, 64, 7, 7, 136, 1, 1, 1, 0, "bf16", "f32"),
+    ConvShape(1, 16, 13, 13, 24, 5, 5, 1, 2, "bf16", "f32"),
+    ConvShape(2, 8, 10, 9, 16, 3, 2, 1, 0, "bf16", "f32"),
+    ConvShape(1, 3, 30, 26, 64, 7, 7, 2, 3, "bf16", "f32"),     # C=3: element-wise gather
+    ConvShape(1, 24, 8, 8, 20, 3, 3, 1, 1, "f16", "f32"),
+    ConvShape(2, 12, 9, 9, 36, 3, 3, 1, 1, "f32", "f32"),
+    ConvShape(1, 5, 8, 9, 7, 3, 3, 2, 2, "f32", "f32"),          # odd everything, scalar stores
+    ConvShape(1, 40, 6, 6, 30, 1, 1, 2, 0, "bf16", "bf16"),
+]
+
+
+def _run_small(torch, helpers, **opts):
+    tenants = [helpers.Tenant(s, synth.gen_input(90, t, 0, s), synth.gen_weight(90, t, 0, s)) for t, s in enumerate(SMALL)]
+    plan = helpers.plan_for(tenants, **opts)
+    sc.st_conv_run(plan)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"small[{i}] {t.shape} opts={opts}")
+    return tenants, plan
+
+
+@pytest.mark.parametrize("tile_cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("split_k", [1, 3])
+def test_every_tile_shape_and_split(torch, tile_cfg, split_k):
+    from tests import helpers
+    _run_small(torch, helpers, tile_cfg=tile_cfg, split_k=split_k)
+
+
+def test_auto_plan_small(torch):
+    from tests import helpers
+    _run_small(torch, helpers)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_config_parity_all_policies(torch, cfg):
+    """Full-size configurations 1-4, element by element, under the three issue policies; the three
+    policies must agree bit for bit (same tiles, same summation order)."""
+    from tests import helpers
+    tenants = helpers.make_tenants(cfg)
+    plan = helpers.plan_for(tenants)
+    sc.st_conv_run(plan)
+    _sync(torch)
+    worst = max(helpers.check_tenant(t, f"cfg{cfg} tenant {i} fused") for i, t in enumerate(tenants))
+    print(f"cfg{cfg}: max |gpu-oracle| = {worst:.3e}")
+    fused = [t.dy.clone() for t in tenants]
+    for t in tenants:
+        t.clear()
+    sc.st_conv_run_time_only(plan)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        assert torch.equal(t.dy, fused[i]), f"time-only differs from fused for tenant {i}"
+        t.clear()
+    streams = [torch.cuda.Stream() for _ in tenants]
+    sc.st_conv_run_space_only(plan, streams)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        assert torch.equal(t.dy, fused[i]), f"space-only differs from fused for tenant {i}"
+
+
+def test_fused_equals_solo_bitwise_and_distinct_weights(torch):
+    """No cross-tenant interaction (Section 4: disjoint graphs): a tenant's fused result equals its result
+    when planned alone with the same tile shape and split; tenants with equal shapes but different weights
+    give different outputs."""
+    from tests import helpers
+    tenants = helpers.make_tenants(3)
+    plan = helpers.plan_for(tenants, tile_cfg=4, split_k=4)
+    sc.st_conv_run(plan)
+    _sync(torch)
+    fused = [t.dy.clone() for t in tenants]
+    assert not torch.equal(fused[1], fused[3])        # same shape (batch 1), different weights and inputs
+    for i, t in enumerate(tenants):
+        t.clear()
+        solo = helpers.plan_for([t], tile_cfg=4, split_k=4)
+        sc.st_conv_run(solo)
+        _sync(torch)
+        assert torch.equal(t.dy, fused[i]), f"tenant {i}: solo != fused"
+
+
+def test_split_k_is_deterministic(torch):
+    from tests import helpers
+    tenants = helpers.make_tenants(2)
+    plan = helpers.plan_for(tenants, split_k=6)
+    sc.st_conv_run(plan)
+    _sync(torch)
+    first = [t.dy.clone() for t in tenants]
+    for _ in range(25):
+        for t in tenants:
+            t.clear()
+        sc.st_conv_run(plan)
+        _sync(torch)
+        for i, t in enumerate(tenants):
+            assert torch.equal(t.dy, first[i])
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"split-K tenant {i}")
+
+
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_epilogue_residual_relu(torch, out_dtype):
+    from tests import helpers
+    shapes = [ConvShape(1, 64, 14, 14, 96, 1, 1, 1, 0, "bf16", out_dtype), ConvShape(2, 32, 9, 9, 48, 3, 3, 1, 1, "bf16", out_dtype)]
+    tenants = []
+    for t, s in enumerate(shapes):
+        res = synth.to_storage(synth.uniform_pm1(synth.stream_state(91, t, 0, 3), s.N * s.K * s.P * s.Q), out_dtype)
+        tenants.append(helpers.Tenant(s, synth.gen_input(91, t, 0, s), synth.gen_weight(91, t, 0, s, 2.0),
+                                      residual=res.reshape(s.N, s.K, s.P, s.Q), relu=True))
+    for opts in ({}, {"tile_cfg": 4, "split_k": 2}):
+        for t in tenants:
+            t.clear()
+        plan = helpers.plan_for(tenants, **opts)
+        sc.st_conv_run(plan)
+        _sync(torch)
+        for i, t in enumerate(tenants):
+            helpers.check_tenant(t, f"epilogue tenant {i} {opts}")
+            assert (t.result() >= 0).all()
+
+
+def test_rebind_and_empty_plan(torch):
+    from tests import helpers
+    empty = sc.st_conv_plan([])
+    sc.st_conv_run(empty)
+    sc.st_conv_run_time_only(empty)
+    sc.st_conv_run_space_only(empty, [torch.cuda.Stream()])
+    assert sc.st_conv_plan_info(empty).n_items == 0
+    a, b = helpers.make_tenants(1)
+    plan = helpers.plan_for([a])
+    sc.st_conv_run(plan)
+    _sync(torch)
+    helpers.check_tenant(a, "before rebind")
+    sc.st_conv_plan_rebind(plan, 0, x=b.dx, w=b.dw, y=b.dy)
+    sc.st_conv_run(plan)
+    _sync(torch)
+    helpers.check_tenant(b, "after rebind")
+
+
+def test_maxpool(torch):
+    from oracle import oracle
+    from tests import helpers
+    x = synth.to_storage(synth.uniform_pm1(synth.stream_state(92, 0, 0, 1), 2 * 24 * 15 * 14), "bf16").reshape(2, 24, 15, 14)
+    dx = helpers.to_device_nhwc(x, "bf16")
+    dy = torch.zeros((2, 8, 7, 24), dtype=torch.bfloat16, device="cuda")
+    sc.st_maxpool_nhwc(dx, dy, 2, 15, 14, 24, 3, 2, 1, "bf16")
+    _sync(torch)
+    assert np.array_equal(helpers.from_device_nhwc(dy), oracle.maxpool2d(x, 3, 2, 1))
