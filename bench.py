@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused multi-tenant convolution launch on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-sweep] [--no-cpu]
+
+A step is one pass of the hot path over one batch of synthetic input: every tenant's layer (or, for
+configuration 5, every tenant's 53-layer stack) executed through cached plans, inputs resident in HBM.
+Prints ONE JSON line.  `value` is aggregate conv TFLOP/s of the fused (space-time) policy on the
+headline workload; `policies` and `per_config` carry the time-only and space-only baselines and the
+other configurations; `roofline` is measured with HIP events on the launch stream; `cpu_baseline` is
+the fp64 oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16/fp16 MFMA
+PEAK_F32_TFLOPS = 157.3       # MI355X fp32 matrix
+PEAK_HBM_GBS = 8000.0
+PAPER_CONTEXT = {"space_time_over_space_only_geomean": 3.23, "space_time_over_time_only_geomean": [7.73, 7.71],
+                 "hardware": "NVIDIA V100 (AWS p3), fp32 SGEMM M=256 N=128 K=1152, 2<=R<=120",
+                 "note": "other hardware and precision; context only"}
+
+CONFIG_TEXT = {
+    1: "configs[0]: 2 tenants, 3x3 s1 p1 32->32 @28x28, batch 1, fp32",
+    2: "configs[1]: 4 tenants, batch 1, bf16 in / fp32 acc, ResNet-50-shaped 3x3 convs 64@56, 128@28, 256@14, 512@7",
+    3: "configs[2]: 8 tenants, 3x3 256->256 @14x14, batch in {1,2,4}, bf16 in / fp32 acc",
+    4: "configs[3]: 16 heterogeneous tenants (1x1, 3x3, 7x7 s2), batch 1..8, bf16 in / fp32 acc",
+    5: "configs[4]: 8 tenants x 53-layer ResNet-50-shaped conv stack, batch 1, bf16, ReLU between layers",
+}
+
+
+def build_workload(cfg: int):
+    """Returns (runner, flops, bytes, n_launches_fused, meta).  runner(policy, stream) issues one step."""
+    import torch
+    from paper_1901_00041_amd import st_conv as sc
+    from paper_1901_00041_amd import synth
+    if cfg == 5:
+        from paper_1901_00041_amd.stack import ResNetStack
+        stack = ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5)
+        return stack.run, stack.flops, stack.bytes, stack.n_launches, {"plan_build_us": stack.plan_build_us,
+                                                                       "n_items": stack.n_items, "keep": stack}
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+    shapes = synth.config_shapes(cfg)
+    keep, descs = [], []
+    for t, s in enumerate(shapes):
+        x = torch.from_numpy(synth.gen_input(cfg, t, 0, s).transpose(0, 2, 3, 1).copy()).to(dt[s.dtype]).cuda()
+        w = torch.from_numpy(synth.gen_weight(cfg, t, 0, s).transpose(0, 2, 3, 1).copy()).to(dt[s.dtype]).cuda()
+        y = torch.empty((s.N, s.P, s.Q, s.K), dtype=dt[s.out_dtype], device="cuda")
+        keep.append((x, w, y))
+        descs.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype, x, w, y))
+    t_plan = []
+    for _ in range(5):
+        t0 = time.perf_counter()
+        plan = sc.st_conv_plan(descs, keep=keep)
+        t_plan.append((time.perf_counter() - t0) * 1e6)
+    info = sc.st_conv_plan_info(plan)
+    streams = [torch.cuda.Stream() for _ in shapes]
+
+    def run(policy: str, stream):
+        if policy == "fused":
+            sc.st_conv_run(plan, stream)
+        elif policy == "time_only":
+            sc.st_conv_run_time_only(plan, stream)
+        else:
+            sc.st_conv_run_space_only(plan, [stream] + streams[1:])
+
+    return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan),
+                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams)}
+
+
+def time_policy(run, policy: str, steps: int, warmup: int):
+    """Wall clock (sync on both sides) and HIP-event time over exactly `steps` steps on one stream."""
+    import torch
+    stream = torch.cuda.Stream()
+    for _ in range(warmup):
+        run(policy, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+        for _ in range(steps):
+            run(policy, stream)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, e0.elapsed_time(e1) / steps
+
+
+def launch_floor_us(n: int = 2000) -> float:
+    import torch
+    from paper_1901_00041_amd import st_conv as sc
+    stream = torch.cuda.Stream()
+    for _ in range(100):
+        sc.st_launch_empty(stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(n):
+        sc.st_launch_empty(stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def cpu_baseline(cfg: int, budget_s: float = 12.0):
+    """The oracle as it stands, timed on this host over whole tenants of the workload until the budget
+    is spent (at least one tenant)."""
+    from oracle import oracle
+    from paper_1901_00041_amd import synth
+    if cfg == 5:
+        steps = synth.resnet50_steps()
+        work = [(5, 0, s.index, s.shape, 2.0) for s in steps]
+        label = "configs[4], tenant 0, conv layers in step order"
+    else:
+        work = [(cfg, t, 0, s, 1.0) for t, s in enumerate(synth.config_shapes(cfg))]
+        label = f"configs[{cfg - 1}], whole tenants in order"
+    done_flops, spent, n_done = 0, 0.0, 0
+    reps = 0
+    while spent < budget_s and reps < 3:
+        for (c, t, layer, s, gain) in work:
+            x = synth.gen_input(c, t, layer, s).astype("float64")
+            w = synth.gen_weight(c, t, layer, s, gain).astype("float64")
+            t0 = time.perf_counter()
+            oracle.conv2d(x, w, s.stride, s.pad)
+            spent += time.perf_counter() - t0
+            done_flops += s.flops
+            n_done += 1
+            if spent >= budget_s:
+                break
+        reps += 1
+    return {"value": done_flops / spent / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{label}: {n_done} layer evaluations, {done_flops / 1e9:.2f} GFLOP in {spent:.1f} s (fp64 direct conv, gcc -O2, OpenMP)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-sweep", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (tenants are independent; sharding is placement only). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1901_00041_amd import st_conv as sc
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sc.lib()
+    torch.cuda.set_device(0)
+    steps = args.steps if args.steps is not None else (200 if args.config == 5 else 2000)
+    warmup = args.warmup if args.warmup is not None else (20 if args.config == 5 else 200)
+
+    floor_us = launch_floor_us()
+
+    def measure(cfg: int, k: int, w: int):
+        run, flops, nbytes, n_launch, meta = build_workload(cfg)
+        out = {"flops": flops, "algorithmic_bytes": nbytes, "plan_build_us": round(meta["plan_build_us"], 1),
+               "work_items": meta["n_items"], "fused_launches_per_step": n_launch}
+        for pol in ("fused", "time_only", "space_only"):
+            wall_ms, ev_ms = time_policy(run, pol, k, w)
+            out[pol] = {"ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12}
+        out["speedup_vs_time_only"] = out["time_only"]["ms_per_step"] / out["fused"]["ms_per_step"]
+        out["speedup_vs_space_only"] = out["space_only"]["ms_per_step"] / out["fused"]["ms_per_step"]
+        out["pct_bf16_mfma_peak"] = 100.0 * out["fused"]["tflops"] / PEAK_BF16_TFLOPS
+        return out
+
+    head = measure(args.config, steps, warmup)
+    fused = head["fused"]
+    # roofline of the dominant kernel (the fused conv kernel), from HIP events on its stream
+    ev_s = fused["event_ms_per_step"] * 1e-3 / head["fused_launches_per_step"]
+    ai = head["flops"] / head["algorithmic_bytes"]
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if args.config == 1:
+        ridge = PEAK_F32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if ai >= ridge:
+        peak = PEAK_F32_TFLOPS if args.config == 1 else PEAK_BF16_TFLOPS
+        ach = head["flops"] / head["fused_launches_per_step"] / ev_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None}
+    else:
+        ach = head["algorithmic_bytes"] / head["fused_launches_per_step"] / ev_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                "traffic": None}
+    roof["kernel"] = "st_conv_kernel (fused launch)"
+    roof["avg_launch_us"] = ev_s * 1e6
+    roof["arithmetic_intensity"] = ai
+
+    per_config = {}
+    if not args.no_sweep:
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                per_config[str(cfg)] = head
+                continue
+            try:
+                per_config[str(cfg)] = measure(cfg, 40 if cfg == 5 else 500, 5 if cfg == 5 else 50)
+            except Exception as e:  # a configuration that cannot run is reported, not hidden
+                per_config[str(cfg)] = {"error": repr(e)}
+        ok = [v for v in per_config.values() if "error" not in v]
+        if ok:
+            import math
+            per_config["geomean_speedup_vs_time_only"] = math.exp(sum(math.log(v["speedup_vs_time_only"]) for v in ok) / len(ok))
+            per_config["geomean_speedup_vs_space_only"] = math.exp(sum(math.log(v["speedup_vs_space_only"]) for v in ok) / len(ok))
+
+    line = {
+        "metric": "aggregate conv TFLOP/s (% bf16 MFMA peak) + speedup vs time-only/space-only",
+        "value": fused["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": fused["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
+        "config": {"workload": CONFIG_TEXT[args.config], "policy": "fused space-time launch, cached plan",
+                   "tenants": __import__("paper_1901_00041_amd.synth", fromlist=["x"]).N_TENANTS[args.config]},
+        "pct_bf16_mfma_peak": head["pct_bf16_mfma_peak"],
+        "speedup_vs_time_only": head["speedup_vs_time_only"], "speedup_vs_space_only": head["speedup_vs_space_only"],
+        "policies": {k: head[k] for k in ("fused", "time_only", "space_only")},
+        "launch_floor_us": floor_us, "plan_build_us": head["plan_build_us"], "work_items": head["work_items"],
+        "gpu_max_hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "default(4)"),
+        "roofline": roof,
+        "paper_context": PAPER_CONTEXT,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.config)
+    if per_config:
+        line["per_config"] = {k: (v if not isinstance(v, dict) else {kk: vv for kk, vv in v.items() if kk != "keep"})
+                              for k, v in per_config.items()}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

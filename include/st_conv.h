@@ -71,7 +71,7 @@ typedef struct st_plan_opts {
   int32_t split_k;       /* 0 = choose per tenant; >= 1 forces that factor (clamped to the K steps)  */
   int32_t order;         /* 0 = longest work item first (default); 1 = tenant-major                  */
   int32_t host_only;     /* 1 = build the tables on the host only (no device calls); run => error    */
-  int32_t target_items;  /* 0 = default; else desired number of work items in the fused launch       */
+  int32_t target_items;  /* 0 = default (512); else workgroup slots the planner's cost model fills     */
   int32_t reserved[3];   /* must be 0                                                                */
 } st_plan_opts;
 
@@ -94,7 +94,7 @@ typedef struct st_tenant_info {
   int32_t MT, NT;              /* pixels and filters per tile                               */
   int32_t tiles_m, tiles_n;
   int32_t split_k;             /* slices of Kgemm per output tile                           */
-  int32_t k_steps;             /* K steps (of st_k_step_bytes() bytes per row) over Kgemm   */
+  int32_t k_steps;             /* K steps (of the tile shape's k_step_bytes per row) over Kgemm */
   int32_t k_steps_per_split;   /* ceil(k_steps / split_k); the last slice may be shorter    */
   int64_t item_begin;          /* slice [item_begin, item_begin+item_count) of the          */
   int64_t item_count;          /*   tenant-major work list belongs to this tenant           */
@@ -122,6 +122,14 @@ st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, const st_pl
 /* Space-time policy (Section 4, Figure 6): one launch, grid = number of work items. */
 st_status st_conv_run(const st_plan* plan, void* hip_stream);
 
+/* The fused launch with in-kernel time stamps, for occupancy-per-tenant and latency reports (the
+ * per-kernel monitoring Section 4 asks of the scheduler).  Synchronous, allocates a scratch buffer: a
+ * diagnostic, not part of the run path.  stamps (HOST pointer) receives 8 uint64 per work item, in
+ * fused work-list order: [0] shader-clock at start, [1] first operands staged, [2] K loop done,
+ * [3] tile stored (0 for split-K slices that did not do the final reduction), [4] 100 MHz wall clock
+ * at start, [5] hardware id (XCC id << 32 | HW_ID register), [6..7] unused. */
+st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream, uint64_t* stamps, int64_t capacity);
+
 /* Time-only policy (Section 3, Figure 6): one launch per tenant on one in-order stream, no host
  * synchronisation in between.  Same kernel, same tiles, same work items as st_conv_run. */
 st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream);
@@ -147,10 +155,10 @@ st_status st_conv_plan_worklist(const st_plan* plan, int32_t which, const st_wor
                                 int64_t* n_items);
 void st_conv_plan_destroy(st_plan* plan);
 
-/* Tile family: shape of config `index` (pixels x filters); returns ST_ERR_INVALID_ARG past the end. */
-st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT);
+/* Tile family: shape of config `index` (pixels x filters) and the bytes of the reduction index it
+ * stages per row per K step; returns ST_ERR_INVALID_ARG past the end. */
+st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT, int32_t* k_step_bytes);
 int32_t st_tile_count(void);
-int32_t st_k_step_bytes(void);
 
 /* 3x3 / stride 2 / pad 1 style max-pool on an NHWC tensor, the one non-convolution step between the
  * stem and the first bottleneck of a ResNet-50-shaped stack.  x: N*H*W*C, y: N*P*Q*C elements of

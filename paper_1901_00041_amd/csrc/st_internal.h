@@ -7,24 +7,30 @@
 namespace st {
 
 constexpr int kThreads = 256;      // workgroup size of every conv kernel: 4 wavefronts of 64
-constexpr int kKStepBytes = 64;    // bytes of the reduction dimension staged per row per K step
 constexpr int kNumCUs = 256;       // MI355X
+constexpr int kProfSlots = 8;      // 64-bit stamps per work item in a profiled launch
 
 // Tile family.  MT = output pixels (rows of the im2col matrix), NT = filters per workgroup tile.
 // The 4 wavefronts form a WPX x WCH grid; MF is the MFMA block edge (32 -> 32x32 blocks,
-// 16 -> 16x16 blocks).
+// 16 -> 16x16 blocks); KB = bytes of the reduction index staged per row per K step; D = K steps of
+// global loads kept in flight in registers.
 struct TileShape {
-  int MT, NT, WPX, WCH, MF;
+  int MT, NT, WPX, WCH, MF, KB, D;
 };
 constexpr int kNumTileCfgs = 6;
 constexpr TileShape kTileShapes[kNumTileCfgs] = {
-    {128, 128, 2, 2, 32},  // 0: wave tile 64x64
-    {128, 64, 2, 2, 32},   // 1: wave tile 64x32
-    {64, 128, 2, 2, 32},   // 2: wave tile 32x64
-    {64, 64, 2, 2, 32},    // 3: wave tile 32x32
-    {32, 64, 2, 2, 16},    // 4: wave tile 16x32
-    {16, 64, 1, 4, 16},    // 5: wave tile 16x16
+    {128, 128, 2, 2, 32, 128, 2},  // 0: wave tile 64x64
+    {128, 64, 2, 2, 32, 128, 2},   // 1: wave tile 64x32
+    {64, 128, 2, 2, 32, 128, 2},   // 2: wave tile 32x64
+    {64, 64, 2, 2, 32, 128, 4},    // 3: wave tile 32x32
+    {32, 64, 2, 2, 16, 128, 4},    // 4: wave tile 16x32
+    {16, 64, 1, 4, 16, 128, 4},    // 5: wave tile 16x16
 };
+constexpr int smem_need(int c) { return 2 * (kTileShapes[c].MT + kTileShapes[c].NT) * (kTileShapes[c].KB + 16); }
+constexpr int kSmemBytes = 73728;  // LDS per workgroup: the largest of the family (checked per tile)
+// tile shapes that also exist as element-wise-gather kernels (channel count not a multiple of the
+// 16-byte vector width); the planner maps such tenants onto one of them
+constexpr bool kGenericCfg[kNumTileCfgs] = {false, true, false, true, false, false};
 
 // Device-side tenant record, read through scalar loads by every workgroup of that tenant.
 struct TenantDev {
@@ -40,12 +46,16 @@ struct TenantDev {
   int32_t cfg, split_k, k_steps, k_steps_per_split;
   int32_t tiles_m, tiles_n;
   int32_t vec_ok;        // 1: C is a multiple of the 16-byte vector width, gathers use 16-byte loads
-  int32_t pad_;
+  int32_t tap_uniform;   // 1: C is a multiple of the K step, so each step lies within one filter tap
+  int32_t shift_c, shift_s;   // floor(n/d) = ((n * magic) >> 31) >> shift, for d = C and d = S
+  uint32_t magic_c, magic_s;
+  uint32_t x_bytes, w_bytes;  // buffer sizes for bounds-checked loads
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 
 // Launchers implemented in st_kernels.hip.  All asynchronous; return the hipError_t as int.
-int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream);
+int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
+                uint64_t* prof_dev);
 int launch_empty(void* stream);
 int launch_maxpool(const void* x, void* y, int N, int H, int W, int C, int P, int Q, int win, int stride,
                    int pad, int dtype, void* stream);

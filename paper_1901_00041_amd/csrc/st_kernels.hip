@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 #include "st_internal.h"
 
 namespace st {
@@ -24,8 +26,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KB = kKStepBytes;   // bytes per row per K step
-constexpr int ROWB = KB + 16;     // LDS row pitch: the 16-byte pad spreads rows over all banks
 
 template <int DT> struct ElemOf;
 template <> struct ElemOf<ST_DT_F32> { static constexpr int ES = 4; };
@@ -77,6 +77,41 @@ template <> struct Mma<ST_DT_F32, 16> {
   }
 };
 
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+// short-circuit "any": f(0) || f(1) || ... || f(N-1), each f called with an integral_constant
+template <int... Is, class F>
+__device__ __forceinline__ bool static_any_impl(std::integer_sequence<int, Is...>, F&& f) {
+  return (f(std::integral_constant<int, Is>{}) || ...);
+}
+template <int N, class F>
+__device__ __forceinline__ bool static_any(F&& f) {
+  return static_any_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+// nested conditionals: if (n > 0) { f(0); if (n > 1) { f(1); ... } } up to N levels
+template <int I, int N, class F>
+__device__ __forceinline__ void static_nest_impl(int n, F&& f) {
+  if constexpr (I < N) {
+    if (n > I) {
+      f(std::integral_constant<int, I>{});
+      static_nest_impl<I + 1, N>(n, static_cast<F&&>(f));
+    }
+  }
+}
+template <int N, class F>
+__device__ __forceinline__ void static_nest(int n, F&& f) {
+  static_nest_impl<0, N>(n, static_cast<F&&>(f));
+}
+
 // ---- output conversion ---------------------------------------------------------------------------
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -95,52 +130,86 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
   return (float)__builtin_bit_cast(_Float16, b);
 }
 
+// ---- cache-coherent partial-tile traffic for split-K -------------------------------------------------
+// Split-K partial tiles travel between workgroups that may sit on different XCDs, whose L2 caches are
+// not coherent with each other.  Instead of fences that write back and invalidate a whole L2, the
+// partials themselves are stored and loaded with device-scope coherence (sc1: write through / miss
+// always), so the only ordering needed is "my stores have completed" before the arrival counter is
+// bumped.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+constexpr int kAuxDeviceCoherent = 16;   // sc1
+
+// floor(n / d) for 0 <= n < 2^31 with the planner's multiplier m = floor(2^(31+L)/d)+1, L = ceil(log2 d)
+__device__ __forceinline__ int fast_div(int n, uint32_t m, int L) {
+  return (int)((uint32_t)(((uint64_t)(uint32_t)n * m) >> 31) >> L);
+}
+
+constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every buffer: the load returns 0
+
 // ---- one workgroup tile --------------------------------------------------------------------------
-template <int MT, int NT, int WPX, int WCH, int MF, int DT>
-__device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item it, char* smem) {
+// MT x NT output tile, 4 wavefronts as WPX x WCH, MFMA block edge MF, KB bytes of the reduction index
+// staged per row per step, D steps of global loads kept in flight in registers ahead of the LDS
+// double buffer.  All global loads are buffer loads whose out-of-range lanes return zero, so padding,
+// ragged tiles and the end of the K range cost no branches.  GENERIC selects element-wise gathers for
+// tensors whose channel count is not a multiple of the 16-byte vector width (e.g. C = 3).
+template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC>
+__device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int ES = ElemOf<DT>::ES;
   constexpr int VEC = 16 / ES;          // elements per 16-byte vector
   constexpr int KT = KB / ES;           // elements of K per step
+  constexpr int ROWB = KB + 16;         // LDS row pitch: the 16-byte pad spreads rows over all banks
+  constexpr int CH = KB / 16;           // 16-byte chunks per row
+  constexpr int RPP = kThreads / CH;    // rows staged per pass of the workgroup
   constexpr int WM = MT / WPX, WN = NT / WCH;
   constexpr int BM = WM / MF, BN = WN / MF;
-  constexpr int A_IT = (MT + 63) / 64, B_IT = (NT + 63) / 64;
+  constexpr int A_IT = (MT + RPP - 1) / RPP, B_IT = (NT + RPP - 1) / RPP;
   constexpr int SUBB = (MF == 32) ? 32 : 64;   // row bytes one MFMA sub-step consumes
   constexpr int NSUB = KB / SUBB;
+  static_assert(D % 2 == 0, "D must be even so that register slots and LDS buffers are both static");
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
   static_assert(WPX * WCH == 4 && WM % MF == 0 && WN % MF == 0, "bad tile shape");
+  static_assert(2 * (MT + NT) * ROWB <= kSmemBytes, "tile does not fit the LDS allocation");
 
   char* sA = smem;                          // [2][MT][ROWB]  patches
   char* sB = smem + 2 * MT * ROWB;          // [2][NT][ROWB]  filters
 
   const int tid = threadIdx.x;
-  const int chunk = tid & 3;     // which 16 bytes of the 64-byte row slab this thread stages
-  const int row0 = tid >> 2;     // 0..63
+  if (prof && tid == 0) {
+    prof[0] = __builtin_readcyclecounter();
+    prof[4] = wall_clock64();
+    prof[5] = ((uint64_t)__builtin_amdgcn_s_getreg(0x1814) << 32) | (uint32_t)__builtin_amdgcn_s_getreg(0xF804);
+  }
+  const int chunk = tid % CH;    // which 16 bytes of the row slab this thread stages
+  const int row0 = tid / CH;
   const int m0 = (int)it.tile_m * MT;
   const int n0 = (int)it.tile_n * NT;
-  const char* __restrict__ xg = (const char*)T.x;
-  const char* __restrict__ wg = (const char*)T.w;
   const int C = T.C, H = T.H, W = T.W, S = T.S, Kg = T.Kg;
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(T.x, T.x_bytes);
+  const __amdgpu_buffer_rsrc_t rw = make_rsrc(T.w, T.w_bytes);
 
-  // K-step range of this work item
+  // K-step range of this work item; loads at or past klimit are suppressed
   const int ks_begin = (int)it.k_split_idx * T.k_steps_per_split;
   int ks_end = ks_begin + T.k_steps_per_split;
   if (ks_end > T.k_steps) ks_end = T.k_steps;
+  const int nsteps = ks_end - ks_begin;
+  const int klimit = (ks_end * KT < Kg) ? ks_end * KT : Kg;
 
   // per-thread patch rows
   int a_base[A_IT], a_h0[A_IT], a_w0[A_IT];
-  bool a_ok[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
-    const int row = row0 + i * 64;
+    const int row = row0 + i * RPP;
     const int m = m0 + row;
-    a_ok[i] = (row < MT) && (m < T.M);
-    const int mm = a_ok[i] ? m : 0;
+    const bool ok = (row < MT) && (m < T.M);
+    const int mm = ok ? m : 0;
     const int n = mm / T.PQ;
     const int pq = mm - n * T.PQ;
     const int p = pq / T.Q;
     const int q = pq - p * T.Q;
-    a_h0[i] = p * T.stride - T.pad;
+    a_h0[i] = ok ? p * T.stride - T.pad : -(1 << 24);   // a dead row fails every bounds check
     a_w0[i] = q * T.stride - T.pad;
     a_base[i] = ((n * H + a_h0[i]) * W + a_w0[i]) * C;
   }
@@ -148,94 +217,95 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   bool b_ok[B_IT];
 #pragma unroll
   for (int i = 0; i < B_IT; ++i) {
-    const int row = row0 + i * 64;
+    const int row = row0 + i * RPP;
     b_ok[i] = (row < NT) && (n0 + row < T.K);
     b_off[i] = b_ok[i] ? (n0 + row) * Kg : 0;
   }
 
-  // position of this thread's vector in the reduction index k = (r*S + s)*C + c
+  // position of the next vector this thread will fetch, in the reduction index k = (r*S + s)*C + c
   int k_elem = ks_begin * KT + chunk * VEC;
-  int kc = k_elem % C;
-  int krs = k_elem / C;
-  int ks_ = krs % S;
-  int kr = krs / S;
+  int k_step0 = ks_begin * KT;   // first element of the step, uniform over the workgroup
 
-  u32x4 ra[A_IT], rb[B_IT];
+  u32x4 ra[D][A_IT], rb[D][B_IT];
 
-  auto load_global = [&]() {
-    if (T.vec_ok) {
-      const bool kin = k_elem < Kg;
-      const int koff = (kr * W + ks_) * C + kc;
+  // Issue the global loads of the next K step into one register slot, then advance the K position.
+  auto issue = [&](u32x4 (&qa)[A_IT], u32x4 (&qb)[B_IT]) {
+    if constexpr (!GENERIC) {
+      const bool kin = k_elem < klimit;
+      int kr, ksx, koff;
+      if (T.tap_uniform) {
+        // C is a multiple of the K step: the whole step lies in one filter tap, found with scalar math
+        const int rs = fast_div(k_step0, T.magic_c, T.shift_c);
+        kr = fast_div(rs, T.magic_s, T.shift_s);
+        ksx = rs - kr * S;
+        koff = (kr * W + ksx) * C + (k_step0 - rs * C) + chunk * VEC;
+      } else {
+        const int rs = fast_div(k_elem, T.magic_c, T.shift_c);
+        kr = fast_div(rs, T.magic_s, T.shift_s);
+        ksx = rs - kr * S;
+        koff = (kr * W + ksx) * C + (k_elem - rs * C);
+      }
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
-        const bool ok = a_ok[i] && kin && (unsigned)(a_h0[i] + kr) < (unsigned)H && (unsigned)(a_w0[i] + ks_) < (unsigned)W;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (ok) v = *(const u32x4*)(xg + (int64_t)(a_base[i] + koff) * ES);
-        ra[i] = v;
+        const bool ok = kin & ((unsigned)(a_h0[i] + kr) < (unsigned)H) & ((unsigned)(a_w0[i] + ksx) < (unsigned)W);
+        const uint32_t off = ok ? (uint32_t)(a_base[i] + koff) * ES : kInvalidOffset;
+        qa[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
       }
 #pragma unroll
       for (int i = 0; i < B_IT; ++i) {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (b_ok[i] && kin) v = *(const u32x4*)(wg + (int64_t)(b_off[i] + k_elem) * ES);
-        rb[i] = v;
+        const uint32_t off = (b_ok[i] & kin) ? (uint32_t)(b_off[i] + k_elem) * ES : kInvalidOffset;
+        qb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
       }
     } else {
-      // generic gather, element by element (C not a multiple of the vector width, e.g. C = 3)
+      // element-wise gather: every element of the vector has its own (r, s, c)
+      uint32_t ea[A_IT][VEC], eb[B_IT][VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const int ke = k_elem + e;
+        const bool kin = ke < klimit;
+        const int rs = fast_div(ke, T.magic_c, T.shift_c);
+        const int kc = ke - rs * C;
+        const int kr = fast_div(rs, T.magic_s, T.shift_s);
+        const int ksx = rs - kr * S;
+        const int koff = (kr * W + ksx) * C + kc;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+          const bool ok = kin & ((unsigned)(a_h0[i] + kr) < (unsigned)H) & ((unsigned)(a_w0[i] + ksx) < (unsigned)W);
+          const uint32_t off = ok ? (uint32_t)(a_base[i] + koff) * ES : kInvalidOffset;
+          if constexpr (ES == 4) ea[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rx, (int)off, 0, 0);
+          else ea[i][e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (int)off, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+          const uint32_t off = (b_ok[i] & kin) ? (uint32_t)(b_off[i] + ke) * ES : kInvalidOffset;
+          if constexpr (ES == 4) eb[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rw, (int)off, 0, 0);
+          else eb[i][e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rw, (int)off, 0, 0);
+        }
+      }
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
-        uint32_t pk[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const int ke = k_elem + e;
-          uint32_t bits = 0u;
-          if (a_ok[i] && ke < Kg) {
-            const int c = ke % C, rs = ke / C;
-            const int s = rs % S, r = rs / S;
-            const int h = a_h0[i] + r, w = a_w0[i] + s;
-            if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
-              const char* p = xg + (int64_t)(a_base[i] + (r * W + s) * C + c) * ES;
-              bits = (ES == 4) ? *(const uint32_t*)p : (uint32_t)*(const uint16_t*)p;
-            }
-          }
-          if (ES == 4) pk[e] = bits; else pk[e >> 1] |= bits << (16 * (e & 1));
-        }
-        ra[i] = u32x4{pk[0], pk[1], pk[2], pk[3]};
+        if constexpr (ES == 4) qa[i] = u32x4{ea[i][0], ea[i][1], ea[i][2], ea[i][3]};
+        else qa[i] = u32x4{ea[i][0] | (ea[i][1] << 16), ea[i][2] | (ea[i][3] << 16), ea[i][4] | (ea[i][5] << 16), ea[i][6] | (ea[i][7] << 16)};
       }
 #pragma unroll
       for (int i = 0; i < B_IT; ++i) {
-        uint32_t pk[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const int ke = k_elem + e;
-          uint32_t bits = 0u;
-          if (b_ok[i] && ke < Kg) {
-            const char* p = wg + (int64_t)(b_off[i] + ke) * ES;
-            bits = (ES == 4) ? *(const uint32_t*)p : (uint32_t)*(const uint16_t*)p;
-          }
-          if (ES == 4) pk[e] = bits; else pk[e >> 1] |= bits << (16 * (e & 1));
-        }
-        rb[i] = u32x4{pk[0], pk[1], pk[2], pk[3]};
+        if constexpr (ES == 4) qb[i] = u32x4{eb[i][0], eb[i][1], eb[i][2], eb[i][3]};
+        else qb[i] = u32x4{eb[i][0] | (eb[i][1] << 16), eb[i][2] | (eb[i][3] << 16), eb[i][4] | (eb[i][5] << 16), eb[i][6] | (eb[i][7] << 16)};
       }
     }
-  };
-  auto advance_k = [&]() {
     k_elem += KT;
-    kc += KT;
-    while (kc >= C) {
-      kc -= C;
-      if (++ks_ == S) { ks_ = 0; ++kr; }
-    }
+    k_step0 += KT;
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](const u32x4 (&qa)[A_IT], const u32x4 (&qb)[B_IT], int buf) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      const int row = row0 + i * 64;
-      if (row < MT) *(u32x4*)(sA + (buf * MT + row) * ROWB + chunk * 16) = ra[i];
+      const int row = row0 + i * RPP;
+      if (MT % RPP == 0 || row < MT) *(u32x4*)(sA + (buf * MT + row) * ROWB + chunk * 16) = qa[i];
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
-      const int row = row0 + i * 64;
-      if (row < NT) *(u32x4*)(sB + (buf * NT + row) * ROWB + chunk * 16) = rb[i];
+      const int row = row0 + i * RPP;
+      if (NT % RPP == 0 || row < NT) *(u32x4*)(sB + (buf * NT + row) * ROWB + chunk * 16) = qb[i];
     }
   };
 
@@ -254,42 +324,58 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
 #pragma unroll
       for (int v = 0; v < (int)(sizeof(Acc) / 4); ++v) acc[i][j][v] = 0.f;
 
-  if (ks_begin < ks_end) {
-    load_global();
-    store_lds(0);
-    __syncthreads();
-    int buf = 0;
-    for (int ks = ks_begin; ks < ks_end; ++ks) {
-      const bool more = (ks + 1 < ks_end);
-      if (more) {
-        advance_k();
-        load_global();
-      }
-      const char* pa = sA + (buf * MT + wm0 + lrow) * ROWB + lk * 16;
-      const char* pb = sB + (buf * NT + wn0 + lrow) * ROWB + lk * 16;
+  auto compute = [&](int buf) {
+    const char* pa = sA + (buf * MT + wm0 + lrow) * ROWB + lk * 16;
+    const char* pb = sB + (buf * NT + wn0 + lrow) * ROWB + lk * 16;
 #pragma unroll
-      for (int sub = 0; sub < NSUB; ++sub) {
-        u32x4 wf[BN], xf[BM];
+    for (int sub = 0; sub < NSUB; ++sub) {
+      u32x4 wf[BN], xf[BM];
 #pragma unroll
-        for (int j = 0; j < BN; ++j) wf[j] = *(const u32x4*)(pb + j * MF * ROWB + sub * SUBB);
+      for (int j = 0; j < BN; ++j) wf[j] = *(const u32x4*)(pb + j * MF * ROWB + sub * SUBB);
 #pragma unroll
-        for (int i = 0; i < BM; ++i) xf[i] = *(const u32x4*)(pa + i * MF * ROWB + sub * SUBB);
+      for (int i = 0; i < BM; ++i) xf[i] = *(const u32x4*)(pa + i * MF * ROWB + sub * SUBB);
 #pragma unroll
-        for (int i = 0; i < BM; ++i)
+      for (int i = 0; i < BM; ++i)
 #pragma unroll
-          for (int j = 0; j < BN; ++j) acc[i][j] = MMA::run(wf[j], xf[i], acc[i][j]);
-      }
-      if (more) store_lds(buf ^ 1);
-      __syncthreads();
-      buf ^= 1;
+        for (int j = 0; j < BN; ++j) acc[i][j] = MMA::run(wf[j], xf[i], acc[i][j]);
     }
+  };
+
+  if (nsteps > 0) {
+    // Steps 0..D-1 go in flight at once; step s lives in register slot s % D.  Steps past the end of the
+    // K range load nothing (every lane out of range), so no issue below needs a condition.
+    static_for<D>([&](auto J) { issue(ra[decltype(J)::value], rb[decltype(J)::value]); });
+    store_lds(ra[0], rb[0], 0);
+    issue(ra[0], rb[0]);
+    __syncthreads();
+    if (prof && tid == 0) prof[1] = __builtin_readcyclecounter();
+    // one K step: compute from LDS buffer j&1, meanwhile move step k+1 from its register slot to the
+    // other buffer and put step k+1+D in flight in that slot
+    auto step = [&](auto J) {
+      constexpr int j = decltype(J)::value;
+      constexpr int nslot = (j + 1) % D;
+      compute(j & 1);
+      store_lds(ra[nslot], rb[nslot], (j + 1) & 1);
+      issue(ra[nslot], rb[nslot]);
+      __syncthreads();
+    };
+    int k = 0;
+    for (; k + D <= nsteps; k += D) static_for<D>(step);     // whole groups: no exits, exact wait counts
+    // remainder (fewer than D steps), nested so that each step is reached only through the previous one
+    const int rem = nsteps - k;
+    static_nest<D - 1>(rem, step);
   }
+
+  if (prof && tid == 0) prof[2] = __builtin_readcyclecounter();
 
   // ---- split-K: publish the partial tile; the last workgroup to arrive sums all slices in order --
   constexpr int NG = (MF == 32) ? 4 : 1;      // groups of 4 consecutive filters per block per lane
   if (T.split_k > 1) {
     const int tile_id = (int)it.tile_m * T.tiles_n + (int)it.tile_n;
-    f32x4* wsb = (f32x4*)(T.ws + ((int64_t)tile_id * T.split_k + it.k_split_idx) * (MT * NT));
+    constexpr uint32_t kTileBytes = MT * NT * 4;
+    const __amdgpu_buffer_rsrc_t rs =
+        make_rsrc(T.ws + (int64_t)tile_id * T.split_k * (MT * NT), (uint32_t)T.split_k * kTileBytes);
+    const uint32_t my = (uint32_t)it.k_split_idx * kTileBytes;
 #pragma unroll
     for (int i = 0; i < BM; ++i)
 #pragma unroll
@@ -297,35 +383,55 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
           f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          wsb[((i * BN + j) * NG + g) * kThreads + tid] = v;
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs,
+                                                 (((i * BN + j) * NG + g) * kThreads + tid) * 16, my, kAuxDeviceCoherent);
         }
-    __threadfence();
+    __builtin_amdgcn_s_waitcnt(0);       // every store of this thread has completed (written through)
     __syncthreads();
     uint32_t* flag = (uint32_t*)smem;
     if (tid == 0) {
-      const uint32_t old = atomicAdd(&T.counters[tile_id], 1u);
+      const uint32_t old = __hip_atomic_fetch_add(&T.counters[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const uint32_t last = (old == (uint32_t)(T.split_k - 1));
-      if (last) atomicExch(&T.counters[tile_id], 0u);   // ready for the next run
+      if (last) __hip_atomic_store(&T.counters[tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next run
       *flag = last;
     }
     __syncthreads();
     if (*flag == 0u) return;
-    __threadfence();
-    const f32x4* wst = (const f32x4*)(T.ws + (int64_t)tile_id * T.split_k * (MT * NT));
+    // Sum the slices in index order.  Loads are issued in batches (GB groups x SB slices) so that the
+    // device-coherent reads, each a trip to memory, overlap; slices past split_k read as zero.
+    constexpr int NGRP = BM * BN * NG;
+    constexpr int GB = NGRP < 4 ? NGRP : 4;
+    constexpr int SB = 8;
+    static_assert(NGRP % GB == 0, "group batching");
+    const int split = T.split_k;
 #pragma unroll
-    for (int i = 0; i < BM; ++i)
+    for (int g0 = 0; g0 < NGRP; g0 += GB) {
+      f32x4 sum[GB];
 #pragma unroll
-      for (int j = 0; j < BN; ++j)
+      for (int gg = 0; gg < GB; ++gg) sum[gg] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int s0 = 0; s0 < split; s0 += SB) {
+        u32x4 part[SB][GB];
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-          f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-          for (int s = 0; s < T.split_k; ++s) {
-            const f32x4 v = __builtin_nontemporal_load(&wst[(int64_t)s * (MT * NT / 4) + ((i * BN + j) * NG + g) * kThreads + tid]);
-            sum += v;
+        for (int ss = 0; ss < SB; ++ss)
+#pragma unroll
+          for (int gg = 0; gg < GB; ++gg) {
+            const uint32_t voff = (s0 + ss < split) ? (uint32_t)(((g0 + gg) * kThreads + tid) * 16) : kInvalidOffset;
+            part[ss][gg] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (s0 + ss) * (int)kTileBytes, kAuxDeviceCoherent);
           }
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = sum[e];
-        }
+        for (int ss = 0; ss < SB; ++ss)
+#pragma unroll
+          for (int gg = 0; gg < GB; ++gg) sum[gg] += __builtin_bit_cast(f32x4, part[ss][gg]);
+      }
+#pragma unroll
+      for (int gg = 0; gg < GB; ++gg) {
+        constexpr int dummy = 0; (void)dummy;
+        const int grp = g0 + gg;
+        const int i = grp / (BN * NG), j = (grp / NG) % BN, g = grp % NG;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = sum[gg][e];
+      }
+    }
   }
 
   // ---- epilogue: (+ residual) -> ReLU -> cast -> store ---------------------------------------------
@@ -378,38 +484,44 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
         }
       }
   }
+  if (prof && tid == 0) prof[3] = __builtin_readcyclecounter();
 }
 
-constexpr int smem_bytes(int cfg) { return 2 * (kTileShapes[cfg].MT + kTileShapes[cfg].NT) * ROWB; }
-constexpr int kSmemMax = smem_bytes(0);
-
-template <int CFG, int DT>
-__device__ __forceinline__ void run_cfg(const TenantDev& T, const st_work_item it, char* smem) {
+template <int CFG, int DT, bool GENERIC>
+__device__ __forceinline__ void run_cfg(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr TileShape s = kTileShapes[CFG];
-  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, DT>(T, it, smem);
+  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC>(T, it, smem, prof);
 }
 
 template <int DT>
-__device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item it, char* smem) {
-  switch (T.cfg) {
-    case 0: run_cfg<0, DT>(T, it, smem); break;
-    case 1: run_cfg<1, DT>(T, it, smem); break;
-    case 2: run_cfg<2, DT>(T, it, smem); break;
-    case 3: run_cfg<3, DT>(T, it, smem); break;
-    case 4: run_cfg<4, DT>(T, it, smem); break;
-    default: run_cfg<5, DT>(T, it, smem); break;
+__device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+  if (T.vec_ok) {
+    switch (T.cfg) {
+      case 0: run_cfg<0, DT, false>(T, it, smem, prof); break;
+      case 1: run_cfg<1, DT, false>(T, it, smem, prof); break;
+      case 2: run_cfg<2, DT, false>(T, it, smem, prof); break;
+      case 3: run_cfg<3, DT, false>(T, it, smem, prof); break;
+      case 4: run_cfg<4, DT, false>(T, it, smem, prof); break;
+      default: run_cfg<5, DT, false>(T, it, smem, prof); break;
+    }
+  } else {
+    // element-wise gathers exist for the two tile shapes in kGenericCfgs
+    if (T.cfg == 1) run_cfg<1, DT, true>(T, it, smem, prof);
+    else run_cfg<3, DT, true>(T, it, smem, prof);
   }
 }
 
-__global__ __launch_bounds__(kThreads) void st_conv_kernel(const TenantDev* __restrict__ tenants,
-                                                          const st_work_item* __restrict__ items) {
-  __shared__ __attribute__((aligned(16))) char smem[kSmemMax];
+__global__ __launch_bounds__(kThreads, 2) void st_conv_kernel(const TenantDev* __restrict__ tenants,
+                                                          const st_work_item* __restrict__ items,
+                                                          uint64_t* __restrict__ prof_base) {
+  __shared__ __attribute__((aligned(16))) char smem[kSmemBytes];
   const st_work_item it = items[blockIdx.x];
   const TenantDev& T = tenants[it.tenant];
+  uint64_t* prof = prof_base ? prof_base + (size_t)blockIdx.x * kProfSlots : nullptr;
   switch (T.in_dtype) {
-    case ST_DT_BF16: run_dtype<ST_DT_BF16>(T, it, smem); break;
-    case ST_DT_F16: run_dtype<ST_DT_F16>(T, it, smem); break;
-    default: run_dtype<ST_DT_F32>(T, it, smem); break;
+    case ST_DT_BF16: run_dtype<ST_DT_BF16>(T, it, smem, prof); break;
+    case ST_DT_F16: run_dtype<ST_DT_F16>(T, it, smem, prof); break;
+    default: run_dtype<ST_DT_F32>(T, it, smem, prof); break;
   }
 }
 
@@ -454,9 +566,11 @@ __global__ __launch_bounds__(256) void st_maxpool_kernel(const void* __restrict_
   else ((uint16_t*)yv)[idx] = (uint16_t)best_bits;
 }
 
-int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream) {
+int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
+                uint64_t* prof_dev) {
   if (n_items <= 0) return 0;
-  hipLaunchKernelGGL(st_conv_kernel, dim3((unsigned)n_items), dim3(kThreads), 0, (hipStream_t)stream, tenants_dev, items_dev);
+  hipLaunchKernelGGL(st_conv_kernel, dim3((unsigned)n_items), dim3(kThreads), 0, (hipStream_t)stream, tenants_dev, items_dev,
+                     prof_dev);
   return (int)hipGetLastError();
 }
 

@@ -55,6 +55,7 @@ struct st_plan {
   std::vector<hipEvent_t> ev_join;          // one per stream slot used by space-only
 };
 
+
 static int elem_size(int dt) { return dt == ST_DT_F32 ? 4 : 2; }
 
 static st_status validate(const st_conv_desc& d, int t) {
@@ -79,55 +80,120 @@ static st_status validate(const st_conv_desc& d, int t) {
   const int64_t lim = (int64_t)1 << 31;
   const int64_t P = ((int64_t)d.H + 2 * d.pad - d.R) / d.stride + 1, Q = ((int64_t)d.W + 2 * d.pad - d.S) / d.stride + 1;
   const int64_t nx = (int64_t)d.N * d.C * d.H * d.W, nw = (int64_t)d.K * d.C * d.R * d.S, ny = (int64_t)d.N * P * Q * d.K;
-  if (nx >= lim || nw >= lim || ny >= lim || (int64_t)d.pad >= (1 << 20) || (int64_t)d.stride >= (1 << 20))
-    return fail(ST_ERR_UNSUPPORTED, "tenant %d: tensors of 2^31 or more elements are not supported", t);
+  const int64_t es = elem_size(d.in_dtype);
+  if (nx * es >= lim || nw * es >= lim || ny >= lim || d.pad >= (1 << 20) || d.stride >= (1 << 20) ||
+      d.C >= (1 << 20) || d.S >= (1 << 20))
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: x and w must stay below 2^31 bytes, y below 2^31 elements", t);
   return ST_OK;
 }
 
 static int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-// Tile shape and split-K factor for one tenant.  `want` is the number of work items this tenant should
-// contribute so that the whole launch covers the compute units a few times over, in proportion to the
-// tenant's share of the arithmetic.
-static void choose_tile(int64_t M, int64_t Ng, int k_steps, int64_t want, const st_plan_opts& o, int* cfg_out,
-                        int* split_out) {
-  const int min_steps_per_split = 4;
-  const int max_split = std::max(1, std::min(k_steps / min_steps_per_split, 256));
-  int cfg = -1;
-  if (o.tile_cfg > 0) {
-    cfg = o.tile_cfg - 1;
-  } else {
-    double eff[kNumTileCfgs], best_eff = 0.0;
-    int64_t tiles[kNumTileCfgs];
-    for (int c = 0; c < kNumTileCfgs; ++c) {
-      const int64_t tm = cdiv(M, kTileShapes[c].MT), tn = cdiv(Ng, kTileShapes[c].NT);
-      tiles[c] = tm * tn;
-      eff[c] = (double)(M * Ng) / (double)(tm * kTileShapes[c].MT * tn * kTileShapes[c].NT);
-      best_eff = std::max(best_eff, eff[c]);
+// Multiplier and shift with floor(n/d) == ((n*m) >> 31) >> L for every 0 <= n < 2^31 (1 <= d < 2^20).
+static void magic_for(int d, uint32_t* m, int32_t* L) {
+  int l = 0;
+  while ((1 << l) < d) ++l;
+  *L = l;
+  *m = (uint32_t)((((uint64_t)1) << (31 + l)) / (uint64_t)d + 1);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// tile shape and split-K selection
+// ---------------------------------------------------------------------------------------------------
+// Cost of one work item in shader clocks, from in-kernel time stamps on an MI355X (st_conv_run_profiled):
+//   first operands staged | one K step | epilogue | split-K hand-off (write-through, counter, read back).
+// The launch is modelled as list scheduling of the items on kSlots workgroup slots: its duration is about
+// max(longest item, sum of item times / kSlots).  The planner picks, per tenant, the (tile, split) option
+// that minimises that maximum over the whole launch.
+static const double kFirstCost = 3000.0;
+static const double kStepCost[kNumTileCfgs] = {1620.0, 1150.0, 1110.0, 750.0, 640.0, 650.0};
+static const double kEpiCost[kNumTileCfgs] = {5900.0, 3650.0, 4000.0, 2160.0, 1170.0, 680.0};
+static const double kGenericStepFactor = 4.5;   // element-wise gathers are bound by the texture addresser
+static const double kSplitCost = 6500.0, kSplitRoundCost = 2700.0;
+static const int kSlots = 2 * kNumCUs;          // two workgroups resident per compute unit
+static const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+
+struct Option {
+  int cfg, split, steps_per_split;
+  int64_t items;
+  double item_time, area;
+};
+
+static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, int cfg, int split) {
+  Option o;
+  const int k_steps = cdiv(kbytes, kTileShapes[cfg].KB);
+  split = std::max(1, std::min(split, std::min(k_steps, 65535)));
+  const int per = cdiv(k_steps, split);
+  split = cdiv(k_steps, per);          // no empty slice
+  o.cfg = cfg;
+  o.split = split;
+  o.steps_per_split = per;
+  o.items = (int64_t)cdiv(M, kTileShapes[cfg].MT) * cdiv(Ng, kTileShapes[cfg].NT) * split;
+  const double step = kStepCost[cfg] * (vec_ok ? 1.0 : kGenericStepFactor);
+  o.item_time = kFirstCost + per * step + kEpiCost[cfg] +
+                (split > 1 ? kSplitCost + kSplitRoundCost * ((split - 1) / 8) : 0.0);
+  o.area = o.item_time * (double)o.items;
+  return o;
+}
+
+static std::vector<Option> tenant_options(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, const st_plan_opts& o) {
+  std::vector<Option> out;
+  for (int c = 0; c < kNumTileCfgs; ++c) {
+    if (!vec_ok && !kGenericCfg[c]) continue;
+    if (o.tile_cfg > 0) {
+      int forced = o.tile_cfg - 1;
+      if (!vec_ok && !kGenericCfg[forced]) forced = (kTileShapes[forced].MT >= 128) ? 1 : 3;  // nearest gather kernel
+      if (c != forced) continue;
     }
-    // largest tile that still yields enough items without split-K
-    for (int c = 0; c < kNumTileCfgs && cfg < 0; ++c)
-      if (eff[c] >= 0.75 * best_eff && tiles[c] >= want) cfg = c;
-    // otherwise the largest tile that reaches the target with split-K; failing that, the one that gets closest
-    if (cfg < 0) {
-      int64_t best_reach = -1;
-      for (int c = 0; c < kNumTileCfgs; ++c) {
-        if (eff[c] < 0.75 * best_eff) continue;
-        const int64_t reach = std::min<int64_t>(want, tiles[c] * max_split);
-        if (reach > best_reach) { best_reach = reach; cfg = c; }
-      }
+    if (o.split_k >= 1) {
+      out.push_back(make_option(M, Ng, kbytes, vec_ok, c, o.split_k));
+      continue;
+    }
+    int last_split = 0;
+    for (int sp : kSplitChoices) {
+      Option op = make_option(M, Ng, kbytes, vec_ok, c, sp);
+      if (op.split == last_split) continue;             // clamped to the same factor as before
+      if (op.split > 1 && op.steps_per_split < 2) continue;
+      last_split = op.split;
+      out.push_back(op);
     }
   }
-  const int64_t tiles = (int64_t)cdiv(M, kTileShapes[cfg].MT) * cdiv(Ng, kTileShapes[cfg].NT);
-  int split = 1;
-  if (o.split_k >= 1) split = o.split_k;
-  else if (tiles < want) split = (int)std::min<int64_t>(max_split, (want + tiles - 1) / tiles);
-  split = std::max(1, std::min(split, std::min(k_steps, 65535)));
-  // normalise so that no slice is empty
-  const int per = cdiv(k_steps, split);
-  split = cdiv(k_steps, per);
-  *cfg_out = cfg;
-  *split_out = split;
+  return out;
+}
+
+// For a bound `limit` on the item time, each tenant takes its cheapest (smallest area) option that meets
+// the bound, or its fastest option if none does; returns the modelled launch duration.
+static double evaluate(const std::vector<std::vector<Option>>& opts, double limit, int slots, std::vector<int>* pick) {
+  double area = 0.0, longest = 0.0;
+  pick->assign(opts.size(), 0);
+  for (size_t t = 0; t < opts.size(); ++t) {
+    int best = -1, fastest = 0;
+    for (size_t i = 0; i < opts[t].size(); ++i) {
+      const Option& op = opts[t][i];
+      if (op.item_time < opts[t][fastest].item_time) fastest = (int)i;
+      if (op.item_time <= limit && (best < 0 || op.area < opts[t][best].area)) best = (int)i;
+    }
+    if (best < 0) best = fastest;
+    (*pick)[t] = best;
+    area += opts[t][best].area;
+    longest = std::max(longest, opts[t][best].item_time);
+  }
+  return std::max(longest, area / slots);
+}
+
+static void choose_all(const std::vector<std::vector<Option>>& opts, int slots, std::vector<int>* pick) {
+  std::vector<double> limits;
+  for (const auto& v : opts)
+    for (const Option& op : v) limits.push_back(op.item_time);
+  std::sort(limits.begin(), limits.end());
+  limits.erase(std::unique(limits.begin(), limits.end()), limits.end());
+  double best = -1.0;
+  std::vector<int> cur;
+  for (double lim : limits) {
+    const double d = evaluate(opts, lim, slots, &cur);
+    if (best < 0 || d < best) { best = d; *pick = cur; }
+  }
+  if (best < 0) pick->assign(opts.size(), 0);
 }
 
 static void destroy_device(st_plan* p) {
@@ -223,27 +289,32 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       ti.flops = 2 * ti.M * ti.Ngemm * ti.Kgemm;
       ti.bytes = ((int64_t)d.N * d.C * d.H * d.W + ti.Ngemm * ti.Kgemm) * elem_size(d.in_dtype) +
                  ti.M * ti.Ngemm * elem_size(d.out_dtype);
-      ti.k_steps = cdiv(ti.Kgemm * elem_size(d.in_dtype), kKStepBytes);
       p->flops += ti.flops;
       p->bytes += ti.bytes;
     }
-    // tile shape and split-K per tenant, in proportion to each tenant's share of the arithmetic
-    const int64_t target = o.target_items > 0 ? o.target_items : 4 * kNumCUs;
+    // tile shape and split-K per tenant, chosen jointly from the cost model
+    std::vector<std::vector<Option>> options(n_tenants);
+    for (int t = 0; t < n_tenants; ++t) {
+      const st_tenant_info& ti = p->info[t];
+      const bool vec_ok = descs[t].C % (16 / elem_size(descs[t].in_dtype)) == 0;
+      options[t] = tenant_options(ti.M, ti.Ngemm, ti.Kgemm * elem_size(descs[t].in_dtype), vec_ok, o);
+    }
+    std::vector<int> pick;
+    choose_all(options, o.target_items > 0 ? o.target_items : kSlots, &pick);
     int64_t fused_total = 0;
     for (int t = 0; t < n_tenants; ++t) {
       st_tenant_info& ti = p->info[t];
-      const int64_t want = std::max<int64_t>(1, (int64_t)std::llround((double)target * (double)ti.flops / (double)p->flops));
-      int cfg, split;
-      choose_tile(ti.M, ti.Ngemm, ti.k_steps, want, o, &cfg, &split);
-      ti.tile_cfg = cfg;
-      ti.MT = kTileShapes[cfg].MT;
-      ti.NT = kTileShapes[cfg].NT;
+      const Option& op = options[t][pick[t]];
+      ti.tile_cfg = op.cfg;
+      ti.k_steps = cdiv(ti.Kgemm * elem_size(descs[t].in_dtype), kTileShapes[op.cfg].KB);
+      ti.MT = kTileShapes[op.cfg].MT;
+      ti.NT = kTileShapes[op.cfg].NT;
       ti.tiles_m = cdiv(ti.M, ti.MT);
       ti.tiles_n = cdiv(ti.Ngemm, ti.NT);
-      ti.split_k = split;
-      ti.k_steps_per_split = cdiv(ti.k_steps, split);
+      ti.split_k = op.split;
+      ti.k_steps_per_split = op.steps_per_split;
       ti.item_begin = fused_total;
-      ti.item_count = (int64_t)ti.tiles_m * ti.tiles_n * split;
+      ti.item_count = (int64_t)ti.tiles_m * ti.tiles_n * op.split;
       fused_total += ti.item_count;
     }
     if (fused_total >= ((int64_t)1 << 31)) {
@@ -273,7 +344,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
         const st_tenant_info& ti = p->info[it.tenant];
         const int begin = (int)it.k_split_idx * ti.k_steps_per_split;
         const int steps = std::min(ti.k_steps, begin + ti.k_steps_per_split) - begin;
-        return (int64_t)steps * ti.MT * ti.NT;
+        return (int64_t)(steps * kStepCost[ti.tile_cfg] + kEpiCost[ti.tile_cfg]);
       };
       std::stable_sort(p->items_fused.begin(), p->items_fused.end(),
                        [&](const st_work_item& a, const st_work_item& b) { return cost(a) > cost(b); });
@@ -291,6 +362,11 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.cfg = ti.tile_cfg; T.split_k = ti.split_k; T.k_steps = ti.k_steps; T.k_steps_per_split = ti.k_steps_per_split;
       T.tiles_m = ti.tiles_m; T.tiles_n = ti.tiles_n;
       T.vec_ok = (d.C % (16 / elem_size(d.in_dtype)) == 0) ? 1 : 0;
+      T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0) ? 1 : 0;
+      magic_for(d.C, &T.magic_c, &T.shift_c);
+      magic_for(d.S, &T.magic_s, &T.shift_s);
+      T.x_bytes = (uint32_t)((int64_t)d.N * d.C * d.H * d.W * elem_size(d.in_dtype));
+      T.w_bytes = (uint32_t)(ti.Ngemm * ti.Kgemm * elem_size(d.in_dtype));
     }
   } catch (const std::bad_alloc&) {
     delete p;
@@ -316,7 +392,24 @@ extern "C" st_status st_conv_run(const st_plan* plan, void* hip_stream) {
   st_status s = check_runnable(plan);
   if (s != ST_OK) return s;
   if (plan->items_fused.empty()) return ST_OK;
-  ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), hip_stream));
+  ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), hip_stream, nullptr));
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream, uint64_t* stamps, int64_t capacity) {
+  st_status s = check_runnable(plan);
+  if (s != ST_OK) return s;
+  const int64_t n = (int64_t)plan->items_fused.size();
+  if (!stamps || capacity < n * kProfSlots) return fail(ST_ERR_INVALID_ARG, "stamps buffer too small: need %lld entries", (long long)(n * kProfSlots));
+  if (n == 0) return ST_OK;
+  uint64_t* d = nullptr;
+  ST_HIP(hipMalloc((void**)&d, (size_t)n * kProfSlots * 8));
+  hipError_t e = hipMemset(d, 0, (size_t)n * kProfSlots * 8);
+  if (e == hipSuccess) e = (hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, n, hip_stream, d);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
+  if (e == hipSuccess) e = hipMemcpy(stamps, d, (size_t)n * kProfSlots * 8, hipMemcpyDeviceToHost);
+  (void)hipFree(d);
+  if (e != hipSuccess) return hip_fail(e, "st_conv_run_profiled");
   return ST_OK;
 }
 
@@ -325,7 +418,7 @@ extern "C" st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream
   if (s != ST_OK) return s;
   for (size_t t = 0; t < plan->info.size(); ++t) {
     const st_tenant_info& ti = plan->info[t];
-    ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_tenant + ti.item_begin, ti.item_count, hip_stream));
+    ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_tenant + ti.item_begin, ti.item_count, hip_stream, nullptr));
   }
   return ST_OK;
 }
@@ -345,7 +438,7 @@ extern "C" st_status st_conv_run_space_only(const st_plan* plan, void* const* hi
   for (size_t t = 0; t < n; ++t) {
     const st_tenant_info& ti = plan->info[t];
     ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_tenant + ti.item_begin, ti.item_count,
-                                   hip_streams[t % (size_t)n_streams]));
+                                   hip_streams[t % (size_t)n_streams], nullptr));
   }
   for (size_t i = 1; i < used; ++i) {
     ST_HIP(hipEventRecord(plan->ev_join[i], (hipStream_t)hip_streams[i]));
@@ -406,14 +499,15 @@ extern "C" void st_conv_plan_destroy(st_plan* plan) {
   delete plan;
 }
 
-extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT) {
-  if (index < 0 || index >= kNumTileCfgs || !MT || !NT) return fail(ST_ERR_INVALID_ARG, "tile index out of range");
+extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT, int32_t* k_step_bytes) {
+  if (index < 0 || index >= kNumTileCfgs || !MT || !NT || !k_step_bytes)
+    return fail(ST_ERR_INVALID_ARG, "tile index out of range or NULL output");
   *MT = kTileShapes[index].MT;
   *NT = kTileShapes[index].NT;
+  *k_step_bytes = kTileShapes[index].KB;
   return ST_OK;
 }
 extern "C" int32_t st_tile_count(void) { return kNumTileCfgs; }
-extern "C" int32_t st_k_step_bytes(void) { return kKStepBytes; }
 
 extern "C" st_status st_maxpool_nhwc(const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t win,
                                      int32_t stride, int32_t pad, int32_t dtype, void* hip_stream) {

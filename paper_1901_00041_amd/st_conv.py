@@ -18,9 +18,9 @@ ST_LAYOUT_NHWC_KRSC = 0
 ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
-EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only",
+EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
-           "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_k_step_bytes", "st_maxpool_nhwc",
+           "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_status_string", "st_last_error_message"]
 
 
@@ -83,6 +83,7 @@ def lib() -> ctypes.CDLL:
         L.st_conv_plan.argtypes = [P(st_conv_desc), i32, P(st_plan_opts), P(vp)]
         L.st_conv_run.argtypes = [vp, vp]
         L.st_conv_run_time_only.argtypes = [vp, vp]
+        L.st_conv_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
         L.st_conv_plan_rebind.argtypes = [vp, i32, vp, vp, vp, vp]
         L.st_conv_plan_info.argtypes = [vp, P(st_plan_info)]
@@ -90,18 +91,17 @@ def lib() -> ctypes.CDLL:
         L.st_conv_plan_worklist.argtypes = [vp, i32, P(P(st_work_item)), P(i64)]
         L.st_conv_plan_destroy.argtypes = [vp]
         L.st_conv_plan_destroy.restype = None
-        L.st_tile_shape.argtypes = [i32, P(i32), P(i32)]
+        L.st_tile_shape.argtypes = [i32, P(i32), P(i32), P(i32)]
         L.st_tile_count.argtypes = []
-        L.st_k_step_bytes.argtypes = []
         L.st_maxpool_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.st_launch_empty.argtypes = [vp]
         L.st_status_string.argtypes = [i32]
         L.st_status_string.restype = ctypes.c_char_p
         L.st_last_error_message.argtypes = []
         L.st_last_error_message.restype = ctypes.c_char_p
-        for name in ("st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only",
+        for name in ("st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
                      "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info",
-                     "st_conv_plan_worklist", "st_tile_shape", "st_tile_count", "st_k_step_bytes",
+                     "st_conv_plan_worklist", "st_tile_shape", "st_tile_count",
                      "st_maxpool_nhwc", "st_launch_empty"):
             getattr(L, name).restype = i32
         _lib = L
@@ -177,6 +177,15 @@ def st_conv_run(plan: Plan, stream=None) -> None:
     _check(lib().st_conv_run(plan.handle, _stream(stream)), "st_conv_run")
 
 
+def st_conv_run_profiled(plan: Plan, stream=None) -> np.ndarray:
+    """Fused launch with time stamps; returns an (n_items, 8) uint64 array (see st_conv.h)."""
+    n = int(st_conv_plan_info(plan).n_items)
+    out = np.zeros((max(n, 1), 8), dtype=np.uint64)
+    _check(lib().st_conv_run_profiled(plan.handle, _stream(stream), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                                      out.size), "st_conv_run_profiled")
+    return out[:n]
+
+
 def st_conv_run_time_only(plan: Plan, stream=None) -> None:
     _check(lib().st_conv_run_time_only(plan.handle, _stream(stream)), "st_conv_run_time_only")
 
@@ -218,17 +227,13 @@ def st_conv_plan_worklist(plan: Plan, which: int = 0) -> np.ndarray:
 
 
 def st_tile_shape(index: int):
-    mt, nt = ctypes.c_int32(), ctypes.c_int32()
-    _check(lib().st_tile_shape(index, ctypes.byref(mt), ctypes.byref(nt)), "st_tile_shape")
-    return mt.value, nt.value
+    mt, nt, kb = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().st_tile_shape(index, ctypes.byref(mt), ctypes.byref(nt), ctypes.byref(kb)), "st_tile_shape")
+    return mt.value, nt.value, kb.value
 
 
 def st_tile_count() -> int:
     return lib().st_tile_count()
-
-
-def st_k_step_bytes() -> int:
-    return lib().st_k_step_bytes()
 
 
 def st_maxpool_nhwc(x, y, N, H, W, C, win, stride, pad, dtype, stream=None) -> None:
