@@ -126,7 +126,7 @@ def cpu_baseline(cfg: int, budget_s: float = 12.0):
         label = f"configs[{cfg - 1}], whole tenants in order"
     done_flops, spent, n_done = 0, 0.0, 0
     reps = 0
-    while spent < budget_s and reps < 3:
+    while spent < budget_s and reps < 1000:
         for (c, t, layer, s, gain) in work:
             x = synth.gen_input(c, t, layer, s).astype("float64")
             w = synth.gen_weight(c, t, layer, s, gain).astype("float64")
@@ -142,6 +142,19 @@ def cpu_baseline(cfg: int, budget_s: float = 12.0):
             "sample": f"{label}: {n_done} layer evaluations, {done_flops / 1e9:.2f} GFLOP in {spent:.1f} s (fp64 direct conv, gcc -O2, OpenMP)"}
 
 
+def measured_traffic(cfg: int):
+    """HBM bytes per fused launch from the committed counter summary (profiles/hbm_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == str(cfg):
+                return float(f[1]) + float(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +163,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-sweep", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--counters", action="store_true",
+                    help="counter-collection mode for rocprofv3 --pmc: only K fused steps of the workload and K launches of "
+                         "a 64 MiB copy kernel (the known-traffic reference); prints a short JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (tenants are independent; sharding is placement only). "
@@ -164,6 +180,22 @@ def main():
     torch.cuda.set_device(0)
     steps = args.steps if args.steps is not None else (200 if args.config == 5 else 2000)
     warmup = args.warmup if args.warmup is not None else (20 if args.config == 5 else 200)
+
+    if args.counters:
+        run, flops, nbytes, n_launch, meta = build_workload(args.config)
+        k = args.steps if args.steps is not None else 20
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(k):
+            run("fused", None)
+        for _ in range(k):
+            sc.st_launch_copy(src, dst, src.numel(), None)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "counters", "workload": CONFIG_TEXT[args.config], "fused_steps": k,
+                          "conv_launches_per_step": n_launch, "algorithmic_bytes_per_step": nbytes, "flops_per_step": flops,
+                          "copy_launches": k, "copy_bytes_read": src.numel(), "copy_bytes_written": src.numel()}))
+        return
 
     floor_us = launch_floor_us()
 
@@ -195,6 +227,7 @@ def main():
         ach = head["algorithmic_bytes"] / head["fused_launches_per_step"] / ev_s / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                 "traffic": None}
+    roof["traffic"] = measured_traffic(args.config)
     roof["kernel"] = "st_conv_kernel (fused launch)"
     roof["avg_launch_us"] = ev_s * 1e6
     roof["arithmetic_intensity"] = ai

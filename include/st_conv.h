@@ -169,6 +169,10 @@ st_status st_maxpool_nhwc(const void* x, void* y, int32_t N, int32_t H, int32_t 
 /* Launches an empty kernel: measures the launch floor the fused policy pays once. */
 st_status st_launch_empty(void* hip_stream);
 
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned
+ * device memory): a kernel of known traffic against which hardware byte counters are scaled. */
+st_status st_launch_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
+
 const char* st_status_string(st_status s);
 const char* st_last_error_message(void);
 

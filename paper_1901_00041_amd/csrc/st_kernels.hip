@@ -574,6 +574,19 @@ int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int
   return (int)hipGetLastError();
 }
 
+// Plain 16-byte-per-lane copy: the reference kernel for scaling hardware traffic counters.
+__global__ __launch_bounds__(256) void st_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+int launch_copy(const void* src, void* dst, int64_t bytes, void* stream) {
+  const int64_t n16 = bytes / 16;
+  if (n16 <= 0) return 0;
+  const unsigned blocks = (unsigned)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
+  hipLaunchKernelGGL(st_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst, n16);
+  return (int)hipGetLastError();
+}
+
 int launch_empty(void* stream) {
   hipLaunchKernelGGL(st_empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
   return (int)hipGetLastError();

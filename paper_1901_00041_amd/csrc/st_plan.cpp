@@ -528,6 +528,12 @@ extern "C" st_status st_launch_empty(void* hip_stream) {
   return ST_OK;
 }
 
+extern "C" st_status st_launch_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes < 0 || (bytes & 15)) return fail(ST_ERR_INVALID_ARG, "need non-NULL pointers and a multiple of 16 bytes");
+  ST_HIP((hipError_t)launch_copy(src, dst, bytes, hip_stream));
+  return ST_OK;
+}
+
 extern "C" const char* st_status_string(st_status s) {
   switch (s) {
     case ST_OK: return "ST_OK";

@@ -21,7 +21,7 @@ DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
-           "st_launch_empty", "st_status_string", "st_last_error_message"]
+           "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
 
 class st_conv_desc(ctypes.Structure):
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.st_tile_count.argtypes = []
         L.st_maxpool_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.st_launch_empty.argtypes = [vp]
+        L.st_launch_copy.argtypes = [vp, vp, i64, vp]
         L.st_status_string.argtypes = [i32]
         L.st_status_string.restype = ctypes.c_char_p
         L.st_last_error_message.argtypes = []
@@ -102,7 +103,7 @@ def lib() -> ctypes.CDLL:
         for name in ("st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
                      "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info",
                      "st_conv_plan_worklist", "st_tile_shape", "st_tile_count",
-                     "st_maxpool_nhwc", "st_launch_empty"):
+                     "st_maxpool_nhwc", "st_launch_empty", "st_launch_copy"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -147,8 +148,11 @@ class Plan:
         self.destroy()
 
     def destroy(self):
-        if getattr(self, "handle", None):
-            lib().st_conv_plan_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            try:
+                _lib.st_conv_plan_destroy(self.handle)
+            except Exception:      # interpreter shutdown
+                pass
             self.handle = None
 
 
@@ -239,6 +243,10 @@ def st_tile_count() -> int:
 def st_maxpool_nhwc(x, y, N, H, W, C, win, stride, pad, dtype, stream=None) -> None:
     _check(lib().st_maxpool_nhwc(_ptr(x), _ptr(y), N, H, W, C, win, stride, pad, DTYPE_CODE.get(dtype, dtype),
                                  _stream(stream)), "st_maxpool_nhwc")
+
+
+def st_launch_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(lib().st_launch_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "st_launch_copy")
 
 
 def st_launch_empty(stream=None) -> None:

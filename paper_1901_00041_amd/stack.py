@@ -1,0 +1,101 @@
+"""Configuration 5: several tenants, each running a ResNet-50-shaped stack of 53 convolution layers,
+scheduled layer by layer: step s of every tenant goes into one fused launch (one cached plan per step).
+
+Data flow per tenant (no batch-norm): stem conv + ReLU, 3x3/2 max-pool, then per bottleneck
+a = ReLU(conv1(x)), b = ReLU(conv2(a)), out = ReLU(conv3(b) + shortcut), shortcut = x or proj(x).
+Activations are stored as bf16; the residual add and the ReLU run in the conv epilogue on the fp32
+accumulator.  All arithmetic runs in the library's kernels; this module only allocates device memory,
+builds the descriptors and issues the run calls.
+"""
+from __future__ import annotations
+
+import time
+from typing import List
+
+import numpy as np
+
+from . import st_conv as sc
+from . import synth
+
+
+class ResNetStack:
+    def __init__(self, n_tenants: int = 8, cfg: int = 5, batch: int = 1, image: int = 224, seeded_weights: bool = True,
+                 plan_opts=None):
+        import torch
+        self.torch = torch
+        self.n_tenants, self.cfg = n_tenants, cfg
+        self.steps: List[synth.Step] = synth.resnet50_steps(batch, image)
+        dev = "cuda"
+        # activation buffers: one tensor per buffer id holding every tenant (tenant-major), sized for the
+        # largest use of that id
+        need = {}
+        for st in self.steps:
+            s = st.shape
+            need[st.src] = max(need.get(st.src, 0), s.N * s.H * s.W * s.C)
+            need[st.dst] = max(need.get(st.dst, 0), s.N * s.P * s.Q * s.K)
+            if st.pool_after:
+                p = (s.P + 2 - 3) // 2 + 1
+                need[st.pool_dst] = max(need.get(st.pool_dst, 0), s.N * p * p * s.K)
+        self.buf = {i: torch.zeros((n_tenants, n), dtype=torch.bfloat16, device=dev) for i, n in need.items()}
+        # network inputs and weights from the seeded generator
+        s0 = self.steps[0].shape
+        for t in range(n_tenants):
+            x = synth.gen_input(cfg, t, 0, s0)
+            self.buf[0][t, :x.size] = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1)).reshape(-1)).to(torch.bfloat16)
+        self.weights = []          # [step][tenant] device tensors, KRSC
+        for st in self.steps:
+            s, row = st.shape, []
+            for t in range(n_tenants):
+                if seeded_weights:
+                    w = synth.gen_weight(cfg, t, st.index, s, 2.0)
+                    row.append(torch.from_numpy(np.ascontiguousarray(w.transpose(0, 2, 3, 1))).to(torch.bfloat16).to(dev))
+                else:
+                    g = torch.Generator(device=dev).manual_seed(1000 * st.index + t)
+                    row.append((torch.randn((s.K, s.R, s.S, s.C), device=dev, generator=g) *
+                                (2.0 / (s.C * s.R * s.S)) ** 0.5).to(torch.bfloat16))
+            self.weights.append(row)
+        # one plan per step
+        self.plans, t_plan = [], []
+        self.flops = self.bytes = self.n_items = 0
+        for st in self.steps:
+            s = st.shape
+            epi = (sc.ST_EPI_RELU if st.relu else 0) | (sc.ST_EPI_RESIDUAL if st.res is not None else 0)
+            descs = [sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, "bf16", "bf16",
+                                  self.buf[st.src][t], self.weights[st.index][t], self.buf[st.dst][t],
+                                  self.buf[st.res][t] if st.res is not None else None, epi)
+                     for t in range(n_tenants)]
+            t0 = time.perf_counter()
+            plan = sc.st_conv_plan(descs, plan_opts)
+            t_plan.append((time.perf_counter() - t0) * 1e6)
+            self.plans.append(plan)
+            info = sc.st_conv_plan_info(plan)
+            self.flops += int(info.flops)
+            self.bytes += int(info.bytes)
+            self.n_items += int(info.n_items)
+        self.plan_build_us = float(np.median(t_plan))
+        self.n_launches = len(self.steps)
+        self._streams = [torch.cuda.Stream() for _ in range(n_tenants)]
+
+    # ---- execution -----------------------------------------------------------------------------------
+    def run_step(self, i: int, policy: str = "fused", stream=None) -> None:
+        st = self.steps[i]
+        if policy == "fused":
+            sc.st_conv_run(self.plans[i], stream)
+        elif policy == "time_only":
+            sc.st_conv_run_time_only(self.plans[i], stream)
+        else:
+            sc.st_conv_run_space_only(self.plans[i], [stream] + self._streams[1:])
+        if st.pool_after:
+            s = st.shape
+            # all tenants' stem outputs are one contiguous batch: a single pooling launch
+            sc.st_maxpool_nhwc(self.buf[st.dst], self.buf[st.pool_dst], self.n_tenants * s.N, s.P, s.Q, s.K, 3, 2, 1,
+                               "bf16", stream)
+
+    def run(self, policy: str = "fused", stream=None) -> None:
+        for i in range(len(self.steps)):
+            self.run_step(i, policy, stream)
+
+    # ---- access for tests ----------------------------------------------------------------------------
+    def view(self, buf_id: int, tenant: int, n: int, h: int, w: int, c: int):
+        """NHWC view of a tenant's buffer holding an (n,h,w,c) tensor."""
+        return self.buf[buf_id][tenant, : n * h * w * c].view(n, h, w, c)

@@ -196,15 +196,16 @@ def resnet50_steps(batch: int = 1, image: int = 224) -> List[Step]:
 
     No batch-norm.  Data flow: a=ReLU(conv1(x)); b=ReLU(conv2(a)); c=conv3(b); shortcut = x or
     proj(x) (no ReLU); out = ReLU(c + shortcut).  Buffer ids: 0 network input, 1 stem output,
-    2/3 alternate as block input/output, 4 = a, 5 = b, 6 = projection output.
+    7 pooled stem output (input of the first block), 2/3 alternate as block output/input afterwards,
+    4 = a, 5 = b, 6 = projection output.
     """
     steps: List[Step] = []
     h = image
     stem = ConvShape(batch, 3, h, h, 64, 7, 7, 2, 3, BF16, BF16)
-    steps.append(Step(0, "stem", stem, 0, 1, None, True, True, 2))
+    steps.append(Step(0, "stem", stem, 0, 1, None, True, True, 7))
     h = stem.P
     h = (h + 2 - 3) // 2 + 1
-    cur, nxt = 2, 3
+    cur, nxt = 7, 2
     c_in = 64
     for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3))):
         for b in range(blocks):
@@ -223,7 +224,7 @@ def resnet50_steps(batch: int = 1, image: int = 224) -> List[Step]:
             h2 = s2.P
             s3 = ConvShape(batch, width, h2, h2, c_out, 1, 1, 1, 0, BF16, BF16)
             steps.append(Step(len(steps), tag + ".conv3", s3, 5, nxt, res, True))
-            cur, nxt = nxt, cur
+            cur, nxt = nxt, (3 if nxt == 2 else 2)
             c_in, h = c_out, h2
     return steps
 

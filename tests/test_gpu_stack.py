@@ -1,0 +1,66 @@
+"""Configuration 5 on the GPU: per-layer, teacher-forced parity of the ResNet-50-shaped stack.
+
+For every step the oracle receives exactly the bf16 tensors the HIP path fed to that step (downloaded),
+computes that one layer (+ residual, + ReLU) in fp64 without rounding, and the HIP path's bf16 output must
+satisfy max|gpu-ref| <= 1e-2*(|ref|+1) (one bf16 rounding of the result costs 2^-9 relative).
+"""
+import numpy as np
+import pytest
+
+from paper_1901_00041_amd import st_conv as sc
+from paper_1901_00041_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _nchw(t):
+    return t.detach().to("cpu").double().numpy().transpose(0, 3, 1, 2)
+
+
+@pytest.mark.parametrize("policy", ["fused"])
+def test_resnet50_stack_layerwise(policy):
+    import torch
+    from oracle import oracle
+    from paper_1901_00041_amd.stack import ResNetStack
+    n_tenants = 3
+    stack = ResNetStack(n_tenants=n_tenants)
+    assert len(stack.steps) == 53 and stack.flops == n_tenants * 8174272512
+    worst = 0.0
+    for st in stack.steps:
+        s = st.shape
+        xs = [_nchw(stack.view(st.src, t, s.N, s.H, s.W, s.C)) for t in range(n_tenants)]
+        rs = [_nchw(stack.view(st.res, t, s.N, s.P, s.Q, s.K)) if st.res is not None else None for t in range(n_tenants)]
+        stack.run_step(st.index, policy)
+        torch.cuda.synchronize()
+        for t in range(n_tenants):
+            w = synth.gen_weight(5, t, st.index, s, 2.0)
+            ref = oracle.conv_layer(xs[t], w, s.stride, s.pad, rs[t], st.relu)
+            got = _nchw(stack.view(st.dst, t, s.N, s.P, s.Q, s.K))
+            err = np.abs(got - ref)
+            tol = 1e-2 * (np.abs(ref) + 1.0)
+            assert np.isfinite(got).all() and (err <= tol).all(), \
+                f"step {st.index} {st.name} tenant {t}: max err {err.max():.3e}, |ref| max {np.abs(ref).max():.3e}"
+            worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
+            if st.pool_after:
+                p = (s.P + 2 - 3) // 2 + 1
+                pooled = _nchw(stack.view(st.pool_dst, t, s.N, p, p, s.K))
+                assert np.array_equal(pooled, oracle.maxpool2d(got, 3, 2, 1)), "max-pool mismatch"
+    print(f"stack: worst relative error {worst:.3e}")
+    # activations stay finite and non-trivial to the end (He-scaled weights keep the scale)
+    last = stack.steps[-1]
+    out = _nchw(stack.view(last.dst, 0, 1, 7, 7, 2048))
+    assert out.shape == (1, 2048, 7, 7) and np.isfinite(out).all() and out.max() > 0
+
+
+def test_stack_policies_agree_bitwise():
+    import torch
+    from paper_1901_00041_amd.stack import ResNetStack
+    stack = ResNetStack(n_tenants=2, seeded_weights=False)
+    outs = {}
+    for policy in ("fused", "time_only", "space_only"):
+        stack.run(policy, None)
+        torch.cuda.synchronize()
+        last = stack.steps[-1]
+        outs[policy] = stack.buf[last.dst].clone()
+    assert torch.equal(outs["fused"], outs["time_only"]) and torch.equal(outs["fused"], outs["space_only"])
+    assert not torch.equal(outs["fused"][0], outs["fused"][1])     # tenants differ

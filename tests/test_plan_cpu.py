@@ -1,0 +1,203 @@
+"""Host-side tests of the C ABI (no GPU, no compute calls): exports, validation, derived sizes and the
+bit-exact work lists, checked against an independent re-derivation in Python."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1901_00041_amd import st_conv as sc
+from paper_1901_00041_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = dict(x=0x10000, w=0x20000, y=0x30000)
+
+
+def _desc(s, **kw):
+    args = dict(x=FAKE["x"], w=FAKE["w"], y=FAKE["y"], residual=None, epilogue=0)
+    args.update(kw)
+    return sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype,
+                        args["x"], args["w"], args["y"], args["residual"], args["epilogue"])
+
+
+def _host_plan(shapes, **opts):
+    return sc.st_conv_plan([_desc(s) for s in shapes], sc.plan_opts(host_only=1, **opts))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "st_conv.h")).read()
+    declared = set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", header))
+    assert {"st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only"} <= declared
+    lib = ctypes.CDLL(sc.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in st_conv.h but not exported"
+    assert declared == set(sc.EXPORTS), (declared ^ set(sc.EXPORTS))
+
+
+def test_section41_worked_example_dims():
+    # Section 4.1: 3x3, 128 -> 128 channels, 16x16 outputs  =>  M=256, N=128, K=1152
+    p = _host_plan([synth.ConvShape(1, 128, 16, 16, 128, 3, 3, 1, 1)])
+    ti = sc.st_conv_plan_tenant_info(p, 0)
+    assert (ti.P, ti.Q, ti.M, ti.Ngemm, ti.Kgemm, ti.flops) == (16, 16, 256, 128, 1152, 75497472)
+    # Table 1's other two shapes as 1x1 convolutions
+    ti = sc.st_conv_plan_tenant_info(_host_plan([synth.ConvShape(1, 256, 16, 16, 256, 1, 1, 1, 0)]), 0)
+    assert (ti.M, ti.Ngemm, ti.Kgemm) == (256, 256, 256)
+    ti = sc.st_conv_plan_tenant_info(_host_plan([synth.ConvShape(1, 512, 1, 1, 512, 1, 1, 1, 0)]), 0)
+    assert (ti.M, ti.Ngemm, ti.Kgemm) == (1, 512, 512)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_config_totals_match_generator(cfg):
+    shapes = synth.config_shapes(cfg)
+    p = _host_plan(shapes)
+    info = sc.st_conv_plan_info(p)
+    assert info.n_tenants == len(shapes) and info.host_only == 1
+    assert info.flops == sum(s.flops for s in shapes) and info.bytes == sum(s.bytes for s in shapes)
+    for t, s in enumerate(shapes):
+        ti = sc.st_conv_plan_tenant_info(p, t)
+        assert (ti.M, ti.Ngemm, ti.Kgemm) == s.gemm and (ti.P, ti.Q) == (s.P, s.Q)
+
+
+def _expected_tenant_major(plan, n_tenants):
+    """Independent enumeration: tenant, pixel tile, filter tile, K slice, from the per-tenant summary only."""
+    rows = []
+    for t in range(n_tenants):
+        ti = sc.st_conv_plan_tenant_info(plan, t)
+        mt, nt, kb = sc.st_tile_shape(ti.tile_cfg)
+        assert (mt, nt) == (ti.MT, ti.NT)
+        assert ti.tiles_m == -(-ti.M // mt) and ti.tiles_n == -(-ti.Ngemm // nt)
+        assert ti.k_steps_per_split == -(-ti.k_steps // ti.split_k)
+        assert (ti.split_k - 1) * ti.k_steps_per_split < ti.k_steps, "an empty K slice"
+        assert ti.item_begin == len(rows) and ti.item_count == ti.tiles_m * ti.tiles_n * ti.split_k
+        for tm in range(ti.tiles_m):
+            for tn in range(ti.tiles_n):
+                for s in range(ti.split_k):
+                    rows.append((t, s, tm, tn, 0))
+    return np.array(rows, dtype=np.int64).reshape(-1, 5)
+
+
+def _as_rows(items):
+    return np.stack([items[f].astype(np.int64) for f in ("tenant", "k_split_idx", "tile_m", "tile_n", "reserved")], axis=1)
+
+
+@pytest.mark.parametrize("cfg,opts", [(1, {}), (2, {}), (3, {}), (4, {}), (2, {"tile_cfg": 6, "split_k": 5}),
+                                      (4, {"tile_cfg": 1}), (3, {"order": 1}), (4, {"split_k": 3, "target_items": 64})])
+def test_work_lists_bit_exact(cfg, opts):
+    shapes = synth.config_shapes(cfg)
+    p = _host_plan(shapes, **opts)
+    want = _expected_tenant_major(p, len(shapes))
+    tenant_major = _as_rows(sc.st_conv_plan_worklist(p, 1))
+    assert np.array_equal(tenant_major, want)
+    fused = _as_rows(sc.st_conv_plan_worklist(p, 0))
+    assert sc.st_conv_plan_info(p).n_items == len(want) == len(fused)
+    # every (tenant, tile, slice) exactly once: the fused list is a permutation of the tenant-major one
+    assert np.array_equal(np.unique(fused, axis=0), np.unique(want, axis=0)) and len(np.unique(fused, axis=0)) == len(want)
+    if opts.get("order") == 1:
+        assert np.array_equal(fused, want)
+    # K coverage: the slices of a tile tile [0, k_steps) without gap or overlap, and cover Kgemm
+    for t, s in enumerate(shapes):
+        ti = sc.st_conv_plan_tenant_info(p, t)
+        kb = sc.st_tile_shape(ti.tile_cfg)[2]
+        es = 4 if s.dtype == "f32" else 2
+        assert ti.k_steps == -(-ti.Kgemm * es // kb)
+        covered = 0
+        for i in range(ti.split_k):
+            b = i * ti.k_steps_per_split
+            e = min(ti.k_steps, b + ti.k_steps_per_split)
+            assert b == covered and e > b
+            covered = e
+        assert covered == ti.k_steps and covered * kb >= ti.Kgemm * es
+    # determinism: the same descriptors give the same lists
+    p2 = _host_plan(shapes, **opts)
+    assert np.array_equal(_as_rows(sc.st_conv_plan_worklist(p2, 0)), fused)
+
+
+def test_fused_order_longest_first():
+    shapes = synth.config_shapes(4)
+    p = _host_plan(shapes)
+    items = sc.st_conv_plan_worklist(p, 0)
+    steps = []
+    for it in items:
+        ti = sc.st_conv_plan_tenant_info(p, int(it["tenant"]))
+        b = int(it["k_split_idx"]) * ti.k_steps_per_split
+        steps.append((min(ti.k_steps, b + ti.k_steps_per_split) - b, ti.tile_cfg))
+    # within one tile shape, items with more K steps never come later than items with fewer
+    for cfg in set(c for _, c in steps):
+        seq = [s for s, c in steps if c == cfg]
+        assert seq == sorted(seq, reverse=True)
+
+
+def test_tile_family_is_sane():
+    n = sc.st_tile_count()
+    assert n >= 4
+    for i in range(n):
+        mt, nt, kb = sc.st_tile_shape(i)
+        assert mt % 16 == 0 and nt % 16 == 0 and kb in (64, 128, 256)
+    with pytest.raises(sc.StError):
+        sc.st_tile_shape(n)
+
+
+def test_validation_errors():
+    good = synth.ConvShape(1, 16, 8, 8, 16, 3, 3, 1, 1)
+
+    def status(desc, opts=None):
+        try:
+            sc.st_conv_plan([desc], opts or sc.plan_opts(host_only=1))
+        except sc.StError as e:
+            assert str(e)            # message is populated
+            return e.status
+        return sc.ST_OK
+
+    import dataclasses
+    assert status(_desc(good)) == sc.ST_OK
+    for field, val in (("N", 0), ("C", -1), ("H", 0), ("K", 0), ("R", 0), ("stride", 0), ("pad", -1)):
+        assert status(_desc(dataclasses.replace(good, **{field: val}))) == sc.ST_ERR_INVALID_ARG, field
+    assert status(_desc(dataclasses.replace(good, R=11))) == sc.ST_ERR_INVALID_ARG          # empty output
+    assert status(_desc(good, x=None)) == sc.ST_ERR_INVALID_ARG
+    assert status(_desc(good, y=FAKE["x"])) == sc.ST_ERR_INVALID_ARG                        # y aliases x
+    assert status(_desc(good, epilogue=sc.ST_EPI_RESIDUAL)) == sc.ST_ERR_INVALID_ARG       # no residual pointer
+    assert status(_desc(good, epilogue=8)) == sc.ST_ERR_UNSUPPORTED
+    d = _desc(good); d.in_dtype = 7
+    assert status(d) == sc.ST_ERR_UNSUPPORTED
+    d = _desc(good); d.out_dtype = sc.ST_DT_F16            # neither f32 nor in_dtype (bf16)
+    assert status(d) == sc.ST_ERR_UNSUPPORTED
+    d = _desc(good); d.layout = 3
+    assert status(d) == sc.ST_ERR_UNSUPPORTED
+    d = _desc(good); d.reserved = 1
+    assert status(d) == sc.ST_ERR_INVALID_ARG
+    assert status(_desc(synth.ConvShape(64, 1024, 256, 256, 8, 1, 1, 1, 0))) == sc.ST_ERR_UNSUPPORTED   # 2^32 elements
+    assert status(_desc(good), sc.plan_opts(host_only=1, tile_cfg=99)) == sc.ST_ERR_INVALID_ARG
+    # NULL plan output and negative tenant count
+    assert sc.lib().st_conv_plan(None, 0, None, None) == sc.ST_ERR_INVALID_ARG
+    out = ctypes.c_void_p()
+    assert sc.lib().st_conv_plan(None, -1, None, ctypes.byref(out)) == sc.ST_ERR_INVALID_ARG and not out.value
+    assert sc.lib().st_conv_plan(None, 2, None, ctypes.byref(out)) == sc.ST_ERR_INVALID_ARG and not out.value
+
+
+def test_host_only_plan_refuses_to_run_and_empty_plan_is_ok():
+    p = _host_plan(synth.config_shapes(1))
+    with pytest.raises(sc.StError) as e:
+        sc.st_conv_run(p)
+    assert e.value.status == sc.ST_ERR_UNSUPPORTED
+    for fn in (sc.st_conv_run_time_only,):
+        with pytest.raises(sc.StError):
+            fn(p)
+    empty = sc.st_conv_plan([], sc.plan_opts(host_only=1))
+    info = sc.st_conv_plan_info(empty)
+    assert info.n_tenants == 0 and info.n_items == 0 and len(sc.st_conv_plan_worklist(empty, 0)) == 0
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_tenant_info(empty, 0)
+
+
+def test_rebind_checks_on_host_plan():
+    p = _host_plan(synth.config_shapes(1))
+    sc.st_conv_plan_rebind(p, 1, x=0x50000)
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_rebind(p, 2, x=0x50000)            # tenant out of range
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_rebind(p, 0, y=FAKE["x"])          # would alias
+
+
+def test_status_strings():
+    assert sc.lib().st_status_string(0) == b"ST_OK" and sc.lib().st_status_string(2) == b"ST_ERR_UNSUPPORTED"
