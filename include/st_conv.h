@@ -37,7 +37,7 @@ extern "C" {
 typedef enum {
   ST_OK = 0,
   ST_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, empty output, aliasing, bad index   */
-  ST_ERR_UNSUPPORTED = 2,   /* unknown dtype/layout, tensor with >= 2^31 elements, host-only plan run */
+  ST_ERR_UNSUPPORTED = 2,   /* unknown dtype/layout, tensor of 2^31 bytes or more, host-only plan run  */
   ST_ERR_OUT_OF_MEMORY = 3, /* host or device allocation failed                                      */
   ST_ERR_DEVICE = 4         /* any other HIP error (text in st_last_error_message)                   */
 } st_status;
@@ -92,12 +92,14 @@ typedef struct st_tenant_info {
   int64_t bytes;               /* x + w + y, each element once                              */
   int32_t tile_cfg;            /* index into st_tile_shape()                                */
   int32_t MT, NT;              /* pixels and filters per tile                               */
-  int32_t tiles_m, tiles_n;
+  int32_t tiles_m, tiles_n;    /* tiles_m = ceil(M/MT), or N*P*ceil(Q/MT) when row_tiled          */
   int32_t split_k;             /* slices of Kgemm per output tile                           */
   int32_t k_steps;             /* K steps (of the tile shape's k_step_bytes per row) over Kgemm */
   int32_t k_steps_per_split;   /* ceil(k_steps / split_k); the last slice may be shorter    */
   int64_t item_begin;          /* slice [item_begin, item_begin+item_count) of the          */
   int64_t item_count;          /*   tenant-major work list belongs to this tenant           */
+  int32_t row_tiled;           /* 1: pixel tiles are segments of single output rows         */
+  int32_t reserved;
 } st_tenant_info;
 
 typedef struct st_plan_info {
@@ -127,7 +129,8 @@ st_status st_conv_run(const st_plan* plan, void* hip_stream);
  * diagnostic, not part of the run path.  stamps (HOST pointer) receives 8 uint64 per work item, in
  * fused work-list order: [0] shader-clock at start, [1] first operands staged, [2] K loop done,
  * [3] tile stored (0 for split-K slices that did not do the final reduction), [4] 100 MHz wall clock
- * at start, [5] hardware id (XCC id << 32 | HW_ID register), [6..7] unused. */
+ * at start, [5] hardware id (XCC id << 32 | HW_ID register), [6] 100 MHz wall clock at the end,
+ * [7] unused. */
 st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream, uint64_t* stamps, int64_t capacity);
 
 /* Time-only policy (Section 3, Figure 6): one launch per tenant on one in-order stream, no host

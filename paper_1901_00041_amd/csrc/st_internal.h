@@ -17,7 +17,9 @@ constexpr int kProfSlots = 8;      // 64-bit stamps per work item in a profiled 
 struct TileShape {
   int MT, NT, WPX, WCH, MF, KB, D;
 };
-constexpr int kNumTileCfgs = 6;
+constexpr int kNumTileCfgs = 7;
+constexpr int kRowCfg = 6;         // the row tile for few-channel layers (conv_tile_rows): 128 pixels of one
+                                   // output row x 64 filters, one filter row (r) per K step
 constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {128, 128, 2, 2, 32, 128, 2},  // 0: wave tile 64x64
     {128, 64, 2, 2, 32, 128, 2},   // 1: wave tile 64x32
@@ -25,12 +27,13 @@ constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {64, 64, 2, 2, 32, 128, 4},    // 3: wave tile 32x32
     {32, 64, 2, 2, 16, 128, 4},    // 4: wave tile 16x32
     {16, 64, 1, 4, 16, 128, 4},    // 5: wave tile 16x16
+    {128, 64, 2, 2, 32, 64, 2},    // 6: row tile (few input channels), wave tile 64x32
 };
 constexpr int smem_need(int c) { return 2 * (kTileShapes[c].MT + kTileShapes[c].NT) * (kTileShapes[c].KB + 16); }
 constexpr int kSmemBytes = 73728;  // LDS per workgroup: the largest of the family (checked per tile)
 // tile shapes that also exist as element-wise-gather kernels (channel count not a multiple of the
 // 16-byte vector width); the planner maps such tenants onto one of them
-constexpr bool kGenericCfg[kNumTileCfgs] = {false, true, false, true, false, false};
+constexpr bool kGenericCfg[kNumTileCfgs] = {false, true, false, true, false, false, false};
 
 // Device-side tenant record, read through scalar loads by every workgroup of that tenant.
 struct TenantDev {
@@ -49,7 +52,10 @@ struct TenantDev {
   int32_t tap_uniform;   // 1: C is a multiple of the K step, so each step lies within one filter tap
   int32_t shift_c, shift_s;   // floor(n/d) = ((n * magic) >> 31) >> shift, for d = C and d = S
   uint32_t magic_c, magic_s;
+  int32_t shift_sc, shift_kg;   // same for d = S*C and d = Kgemm (row tile only)
+  uint32_t magic_sc, magic_kg;
   uint32_t x_bytes, w_bytes;  // buffer sizes for bounds-checked loads
+  uint32_t y_bytes, pad_;     // size of y (and of the residual) in bytes
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 

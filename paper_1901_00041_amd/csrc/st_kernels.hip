@@ -114,10 +114,7 @@ __device__ __forceinline__ void static_nest(int n, F&& f) {
 
 // ---- output conversion ---------------------------------------------------------------------------
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, (__bf16)f);     // v_cvt_pk_bf16_f32: round to nearest even
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
   return __builtin_bit_cast(float, (uint32_t)b << 16);
@@ -147,6 +144,164 @@ __device__ __forceinline__ int fast_div(int n, uint32_t m, int L) {
 }
 
 constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every buffer: the load returns 0
+
+// ---- epilogue shared by all tile kernels: (+ residual) -> ReLU -> cast -> store ---------------------
+// acc[i][j] is the MF x MF block at pixels wm0 + i*MF, filters wn0 + j*MF of the tile whose first pixel is
+// im2col row m0 and first filter n0; rows at or past m_end are not stored.
+template <int MT, int NT, int BM, int BN, int MF, class Acc>
+__device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
+                                              int wn0, int lrow, int lk, int tid, char* smem, uint64_t* prof = nullptr) {
+  constexpr int NG = (MF == 32) ? 4 : 1;
+  const bool relu = (T.epilogue & ST_EPI_RELU) != 0u;
+  const bool has_res = (T.epilogue & ST_EPI_RESIDUAL) != 0u;
+  const int Kf = T.K;
+  const bool vec4 = (Kf & 3) == 0;
+  if ((Kf & 7) == 0) {
+    // Transpose through LDS: accumulators go to an fp32 [pixel][filter] tile, then every lane handles 16
+    // bytes of one output row, so residual loads and output stores are whole contiguous rows.
+    constexpr int PITCH = NT + 4;   // floats; the pad keeps the 16-byte writes of 16 pixels on distinct banks
+    static_assert(MT * PITCH * 4 <= kSmemBytes, "output tile does not fit the LDS allocation");
+    float* sC = (float*)smem;
+    __syncthreads();                // operand buffers (and the split-K flag) are no longer read
+#pragma unroll
+    for (int i = 0; i < BM; ++i)
+#pragma unroll
+      for (int j = 0; j < BN; ++j)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const int row = wm0 + i * MF + lrow;
+          const int chl = wn0 + j * MF + ((MF == 32) ? (8 * g + 4 * lk) : (4 * lk));
+          *(f32x4*)(sC + row * PITCH + chl) = f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        }
+    __syncthreads();
+    if (prof && tid == 0) prof[7] = __builtin_readcyclecounter();
+    // Branch-free read-back: rows past the tile end or filters past K get an out-of-range offset, which
+    // drops the store (and makes the residual load return zero).
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(has_res ? T.res : T.y, T.y_bytes);
+    if (T.out_dtype == ST_DT_F32) {
+      constexpr int NV = NT / 4;
+      constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+      f32x4 a[IT];
+      uint32_t off[IT];
+#pragma unroll
+      for (int u = 0; u < IT; ++u) {
+        const int v = u * kThreads + tid;
+        const int row = v / NV, cv = v % NV;
+        const int m = m0 + row, ch = n0 + cv * 4;
+        const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+        off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset;
+        a[u] = *(const f32x4*)(sC + (row < MT ? row : 0) * PITCH + cv * 4);
+      }
+      if (has_res) {
+#pragma unroll
+        for (int u = 0; u < IT; ++u) a[u] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
+      }
+#pragma unroll
+      for (int u = 0; u < IT; ++u) {
+        if (relu) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) a[u][e] = a[u][e] > 0.f ? a[u][e] : 0.f;
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a[u]), ry, (int)off[u], 0, 0);
+      }
+    } else {
+      constexpr int NV = NT / 8;
+      constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+      const bool isbf = (T.out_dtype == ST_DT_BF16);
+      f32x4 lo[IT], hi[IT];
+      uint32_t off[IT];
+#pragma unroll
+      for (int u = 0; u < IT; ++u) {
+        const int v = u * kThreads + tid;
+        const int row = v / NV, cv = v % NV;
+        const int m = m0 + row, ch = n0 + cv * 8;
+        const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+        off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
+        const float* src = sC + (row < MT ? row : 0) * PITCH + cv * 8;
+        lo[u] = *(const f32x4*)src;
+        hi[u] = *(const f32x4*)(src + 4);
+      }
+      if (has_res) {
+#pragma unroll
+        for (int u = 0; u < IT; ++u) {
+          const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint16_t h0 = (uint16_t)(r[e >> 1] >> (16 * (e & 1))), h1 = (uint16_t)(r[2 + (e >> 1)] >> (16 * (e & 1)));
+            lo[u][e] += isbf ? bf16_bits_to_f32(h0) : f16_bits_to_f32(h0);
+            hi[u][e] += isbf ? bf16_bits_to_f32(h1) : f16_bits_to_f32(h1);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < IT; ++u) {
+        if (relu) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            lo[u][e] = lo[u][e] > 0.f ? lo[u][e] : 0.f;
+            hi[u][e] = hi[u][e] > 0.f ? hi[u][e] : 0.f;
+          }
+        }
+        u32x4 pk;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          pk[e] = isbf ? ((uint32_t)f32_to_bf16_rne(lo[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(lo[u][2 * e + 1]) << 16))
+                       : ((uint32_t)f32_to_f16_bits(lo[u][2 * e]) | ((uint32_t)f32_to_f16_bits(lo[u][2 * e + 1]) << 16));
+          pk[2 + e] = isbf ? ((uint32_t)f32_to_bf16_rne(hi[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(hi[u][2 * e + 1]) << 16))
+                           : ((uint32_t)f32_to_f16_bits(hi[u][2 * e]) | ((uint32_t)f32_to_f16_bits(hi[u][2 * e + 1]) << 16));
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(pk, ry, (int)off[u], 0, 0);
+      }
+    }
+  } else {
+  #pragma unroll
+    for (int i = 0; i < BM; ++i) {
+      const int m = m0 + wm0 + i * MF + lrow;
+      if (m >= m_end) continue;
+  #pragma unroll
+      for (int j = 0; j < BN; ++j)
+  #pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const int ch = n0 + wn0 + j * MF + ((MF == 32) ? (8 * g + 4 * lk) : (4 * lk));
+          if (ch >= Kf) continue;
+          float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          const int64_t o = (int64_t)m * Kf + ch;
+          const int nv = (Kf - ch < 4) ? (Kf - ch) : 4;
+          if (T.out_dtype == ST_DT_F32) {
+            float* y = (float*)T.y + o;
+            if (has_res) {
+              const float* rp = (const float*)T.res + o;
+              for (int e = 0; e < nv; ++e) v[e] += rp[e];
+            }
+            if (relu)
+              for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            if (vec4) *(f32x4*)y = f32x4{v[0], v[1], v[2], v[3]};
+            else for (int e = 0; e < nv; ++e) y[e] = v[e];
+          } else {
+            uint16_t* y = (uint16_t*)T.y + o;
+            const bool isbf = (T.out_dtype == ST_DT_BF16);
+            if (has_res) {
+              const uint16_t* rp = (const uint16_t*)T.res + o;
+              for (int e = 0; e < nv; ++e) v[e] += isbf ? bf16_bits_to_f32(rp[e]) : f16_bits_to_f32(rp[e]);
+            }
+            if (relu)
+              for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            uint16_t hbits[4];
+            for (int e = 0; e < 4; ++e) hbits[e] = isbf ? f32_to_bf16_rne(v[e]) : f32_to_f16_bits(v[e]);
+            if (vec4) {
+              uint2 pk;
+              pk.x = (uint32_t)hbits[0] | ((uint32_t)hbits[1] << 16);
+              pk.y = (uint32_t)hbits[2] | ((uint32_t)hbits[3] << 16);
+              *(uint2*)y = pk;
+            } else {
+              for (int e = 0; e < nv; ++e) y[e] = hbits[e];
+            }
+          }
+        }
+    }
+  }
+}
 
 // ---- one workgroup tile --------------------------------------------------------------------------
 // MT x NT output tile, 4 wavefronts as WPX x WCH, MFMA block edge MF, KB bytes of the reduction index
@@ -396,7 +551,10 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
       *flag = last;
     }
     __syncthreads();
-    if (*flag == 0u) return;
+    if (*flag == 0u) {
+      if (prof && tid == 0) prof[6] = wall_clock64();
+      return;
+    }
     // Sum the slices in index order.  Loads are issued in batches (GB groups x SB slices) so that the
     // device-coherent reads, each a trip to memory, overlap; slices past split_k read as zero.
     constexpr int NGRP = BM * BN * NG;
@@ -435,56 +593,187 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   }
 
   // ---- epilogue: (+ residual) -> ReLU -> cast -> store ---------------------------------------------
-  const bool relu = (T.epilogue & ST_EPI_RELU) != 0u;
-  const bool has_res = (T.epilogue & ST_EPI_RESIDUAL) != 0u;
-  const int Kf = T.K;
-  const bool vec4 = (Kf & 3) == 0;
+  tile_epilogue<MT, NT, BM, BN, MF>(T, acc, m0, T.M, n0, wm0, wn0, lrow, lk, tid, smem, prof);
+  if (prof && tid == 0) {
+    prof[3] = __builtin_readcyclecounter();
+    prof[6] = wall_clock64();
+  }
+}
+
+// ---- row tile for layers with very few input channels ---------------------------------------------
+// For the 7x7 / stride-2 / 3-channel stem the im2col row of one (pixel, filter row r) is S*C = 21
+// contiguous elements of the NHWC image, at an odd element offset, so neither 16-byte gathers nor the
+// element-wise gather variant are efficient.  This kernel takes one output row segment (up to 128 pixels)
+// x 64 filters per workgroup: the R input rows it needs are copied whole into LDS with aligned 16-byte
+// loads (rows outside the image and the left/right padding are zeros), the 64 filters are copied into
+// an LDS array [filter][r][32] padded with zeros, and the MFMA operands are assembled from LDS, the pixel
+// side with 2-byte reads.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by the planner:
+// 16-bit types, S*C <= 32, W*C*2 a multiple of 16, LDS footprint within the allocation.
+template <int DT>
+__device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+  constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
+  typedef Mma<DT, MF> MMA;
+  typedef typename MMA::Acc Acc;
+  const int tid = threadIdx.x;
+  if (prof && tid == 0) {
+    prof[0] = __builtin_readcyclecounter();
+    prof[4] = wall_clock64();
+    prof[5] = ((uint64_t)__builtin_amdgcn_s_getreg(0x1814) << 32) | (uint32_t)__builtin_amdgcn_s_getreg(0xF804);
+  }
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+  const int lrow = lane & 31, lk = lane >> 5;
+  const int C = T.C, H = T.H, W = T.W, R = T.R, S = T.S, Q = T.Q, Kg = T.Kg;
+  const int SC = S * C;
+  const int qt = (Q + MT - 1) / MT;
+  const int np = (int)it.tile_m / qt;
+  const int q0 = ((int)it.tile_m - np * qt) * MT;
+  const int n = np / T.P, p = np - n * T.P;
+  const int n0 = (int)it.tile_n * NT;
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(T.x, T.x_bytes);
+  const __amdgpu_buffer_rsrc_t rw = make_rsrc(T.w, T.w_bytes);
+
+  // LDS: R image rows, each [pad*C zeros][W*C elements][zeros] starting on a 16-byte boundary, so that
+  // every pixel's patch (which starts stride*C elements after its neighbour's) is 4-byte aligned; then
+  // the filters.
+  const int lpad = T.pad * C * 2;                           // bytes of left padding
+  const int rowb = W * C * 2;                               // bytes of one image row (multiple of 16)
+  const int pitch = ((lpad + rowb + lpad + 15) & ~15) + 64;
+  char* sW = smem + R * pitch;                              // [NT][R][KR] elements
+
+  // 1. put the global loads in flight: all image rows (rows outside the image read as zeros) and the first
+  //    round of filter vectors (the tile's filters are one contiguous run of nf*Kg elements)
+  const int nvr = rowb / 16, total_rows = R * nvr;
+  const int nf = (T.K - n0 < NT) ? (T.K - n0) : NT;
+  const int total_e = nf * Kg;
+  const uint32_t wbase = (uint32_t)n0 * (uint32_t)Kg * 2u;
+  constexpr int RV = 4, RW = 5;                             // vectors per thread per round: image rows, filters
+  u32x4 drow[RV], dw[RW];
+#pragma unroll
+  for (int u = 0; u < RV; ++u) {
+    const int v = u * kThreads + tid;
+    const int r = v / nvr, i = v - r * nvr;
+    const int h = p * T.stride - T.pad + r;
+    const bool ok = (v < total_rows) & ((unsigned)h < (unsigned)H);
+    const uint32_t off = ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
+    drow[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
+  }
+#pragma unroll
+  for (int u = 0; u < RW; ++u)
+    dw[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(wbase + (uint32_t)(u * kThreads + tid) * 16u), 0, 0);
+
+  // 2. zero the padding of the rows and the whole filter array
+  {
+    const int zl = lpad / 2, zr = (pitch - lpad - rowb) / 2;   // elements left / right of the data
+    for (int r = wave; r < R; r += 4)
+      for (int e = lane; e < zl + zr; e += 64) {
+        const int off = (e < zl) ? 2 * e : lpad + rowb + 2 * (e - zl);
+        *(uint16_t*)(smem + r * pitch + off) = 0;
+      }
+    for (int z = tid; z < NT * R * KR * 2 / 16; z += kThreads) *(u32x4*)(sW + z * 16) = u32x4{0u, 0u, 0u, 0u};
+  }
+  // 3. image rows into LDS; the data starts lpad bytes into the row, i.e. 4-byte aligned or 2 bytes off
+  auto put_row_vector = [&](int v, const u32x4& d) {
+    if (v < total_rows) {
+      const int r = v / nvr, i = v - r * nvr;
+      char* dst = smem + r * pitch + lpad + i * 16;
+      if ((lpad & 3) == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) *(uint32_t*)(dst + 4 * e) = d[e];
+      } else {
+        *(uint16_t*)dst = (uint16_t)d[0];
+#pragma unroll
+        for (int e = 0; e < 3; ++e) *(uint32_t*)(dst + 2 + 4 * e) = (d[e] >> 16) | (d[e + 1] << 16);
+        *(uint16_t*)(dst + 14) = (uint16_t)(d[3] >> 16);
+      }
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < RV; ++u) put_row_vector(u * kThreads + tid, drow[u]);
+  for (int v0 = RV * kThreads; v0 < total_rows; v0 += kThreads) {      // rows longer than one round (rare)
+    const int v = v0 + tid;
+    const int r = v / nvr, i = v - r * nvr;
+    const int h = p * T.stride - T.pad + r;
+    const bool ok = (v < total_rows) & ((unsigned)h < (unsigned)H);
+    const uint32_t off = ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
+    put_row_vector(v, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0));
+  }
+  __syncthreads();   // the filter array is zeroed before the scatter below
+  // 4. filters: scatter each element of the contiguous run to [filter][r][s*C+c]
+  auto put_filter_vector = [&](int v, const u32x4& d) {
+    int f = v * 8;
+    if (f < total_e) {
+      int ch = fast_div(f, T.magic_kg, T.shift_kg);
+      const int rem = f - ch * Kg;
+      int r = fast_div(rem, T.magic_sc, T.shift_sc);
+      int j = rem - r * SC;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (f + e < total_e) *(uint16_t*)(sW + ((ch * R + r) * KR + j) * 2) = (uint16_t)(d[e >> 1] >> (16 * (e & 1)));
+        if (++j == SC) { j = 0; if (++r == R) { r = 0; ++ch; } }
+      }
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < RW; ++u) put_filter_vector(u * kThreads + tid, dw[u]);
+  for (int v0 = RW * kThreads; v0 * 8 < total_e; v0 += RW * kThreads) {
+#pragma unroll
+    for (int u = 0; u < RW; ++u)
+      dw[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(wbase + (uint32_t)(v0 + u * kThreads + tid) * 16u), 0, 0);
+#pragma unroll
+    for (int u = 0; u < RW; ++u) put_filter_vector(v0 + u * kThreads + tid, dw[u]);
+  }
+  __syncthreads();
+  if (prof && tid == 0) prof[1] = __builtin_readcyclecounter();
+
+  Acc acc[BM][BN];
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
+
+  // per-lane masks that clear the elements at or past S*C (they belong to the next pixel)
+  uint32_t msk[2][4];
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int j = 16 * half + 8 * lk + 2 * d;
+      msk[half][d] = (j < SC ? 0x0000ffffu : 0u) | (j + 1 < SC ? 0xffff0000u : 0u);
+    }
+  const int nh = (SC + 15) >> 4;     // 16-element halves of a filter row that hold data
+  int qa[BM];
 #pragma unroll
   for (int i = 0; i < BM; ++i) {
-    const int m = m0 + wm0 + i * MF + lrow;
-    if (m >= T.M) continue;
+    int q = q0 + wm0 + i * MF + lrow;
+    q = q < Q ? q : Q - 1;           // columns past the row end repeat the last pixel; they are never stored
+    qa[i] = q * T.stride * C * 2 + lk * 16;
+  }
+  const char* wrow = sW + (wn0 + lrow) * R * (KR * 2) + lk * 16;
+  for (int r = 0; r < R; ++r) {
+    const char* xr = smem + r * pitch;
 #pragma unroll
-    for (int j = 0; j < BN; ++j)
+    for (int half = 0; half < 2; ++half) {
+      if (half < nh) {
+        const u32x4 wf = *(const u32x4*)(wrow + r * (KR * 2) + half * 32);
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        const int ch = n0 + wn0 + j * MF + ((MF == 32) ? (8 * g + 4 * lk) : (4 * lk));
-        if (ch >= Kf) continue;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        const int64_t o = (int64_t)m * Kf + ch;
-        const int nv = (Kf - ch < 4) ? (Kf - ch) : 4;
-        if (T.out_dtype == ST_DT_F32) {
-          float* y = (float*)T.y + o;
-          if (has_res) {
-            const float* rp = (const float*)T.res + o;
-            for (int e = 0; e < nv; ++e) v[e] += rp[e];
-          }
-          if (relu)
-            for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-          if (vec4) *(f32x4*)y = f32x4{v[0], v[1], v[2], v[3]};
-          else for (int e = 0; e < nv; ++e) y[e] = v[e];
-        } else {
-          uint16_t* y = (uint16_t*)T.y + o;
-          const bool isbf = (T.out_dtype == ST_DT_BF16);
-          if (has_res) {
-            const uint16_t* rp = (const uint16_t*)T.res + o;
-            for (int e = 0; e < nv; ++e) v[e] += isbf ? bf16_bits_to_f32(rp[e]) : f16_bits_to_f32(rp[e]);
-          }
-          if (relu)
-            for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-          uint16_t hbits[4];
-          for (int e = 0; e < 4; ++e) hbits[e] = isbf ? f32_to_bf16_rne(v[e]) : f32_to_f16_bits(v[e]);
-          if (vec4) {
-            uint2 pk;
-            pk.x = (uint32_t)hbits[0] | ((uint32_t)hbits[1] << 16);
-            pk.y = (uint32_t)hbits[2] | ((uint32_t)hbits[3] << 16);
-            *(uint2*)y = pk;
-          } else {
-            for (int e = 0; e < nv; ++e) y[e] = hbits[e];
-          }
+        for (int i = 0; i < BM; ++i) {
+          const uint32_t* src = (const uint32_t*)(xr + qa[i] + half * 32);
+          const u32x4 xf = {src[0] & msk[half][0], src[1] & msk[half][1], src[2] & msk[half][2], src[3] & msk[half][3]};
+          acc[i][0] = MMA::run(wf, xf, acc[i][0]);
         }
       }
+    }
   }
-  if (prof && tid == 0) prof[3] = __builtin_readcyclecounter();
+  if (prof && tid == 0) prof[2] = __builtin_readcyclecounter();
+
+  const int m0 = np * Q + q0;
+  const int m_end = np * Q + ((q0 + MT < Q) ? q0 + MT : Q);
+  tile_epilogue<MT, NT, BM, BN, MF>(T, acc, m0, m_end, n0, wm0, wn0, lrow, lk, tid, smem);
+  if (prof && tid == 0) {
+    prof[3] = __builtin_readcyclecounter();
+    prof[6] = wall_clock64();
+  }
 }
 
 template <int CFG, int DT, bool GENERIC>
@@ -505,7 +794,11 @@ __device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item
       default: run_cfg<5, DT, false>(T, it, smem, prof); break;
     }
   } else {
-    // element-wise gathers exist for the two tile shapes in kGenericCfgs
+    // few-channel layers: the row tile when the planner found it eligible, else element-wise gathers
+    // (which exist for the two tile shapes marked in kGenericCfg)
+    if constexpr (DT != ST_DT_F32) {
+      if (T.cfg == kRowCfg) { conv_tile_rows<DT>(T, it, smem, prof); return; }
+    }
     if (T.cfg == 1) run_cfg<1, DT, true>(T, it, smem, prof);
     else run_cfg<3, DT, true>(T, it, smem, prof);
   }

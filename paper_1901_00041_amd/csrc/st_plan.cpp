@@ -81,9 +81,9 @@ static st_status validate(const st_conv_desc& d, int t) {
   const int64_t P = ((int64_t)d.H + 2 * d.pad - d.R) / d.stride + 1, Q = ((int64_t)d.W + 2 * d.pad - d.S) / d.stride + 1;
   const int64_t nx = (int64_t)d.N * d.C * d.H * d.W, nw = (int64_t)d.K * d.C * d.R * d.S, ny = (int64_t)d.N * P * Q * d.K;
   const int64_t es = elem_size(d.in_dtype);
-  if (nx * es >= lim || nw * es >= lim || ny >= lim || d.pad >= (1 << 20) || d.stride >= (1 << 20) ||
+  if (nx * es >= lim || nw * es >= lim || ny * elem_size(d.out_dtype) >= lim || d.pad >= (1 << 20) || d.stride >= (1 << 20) ||
       d.C >= (1 << 20) || d.S >= (1 << 20))
-    return fail(ST_ERR_UNSUPPORTED, "tenant %d: x and w must stay below 2^31 bytes, y below 2^31 elements", t);
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: x, w and y must each stay below 2^31 bytes", t);
   return ST_OK;
 }
 
@@ -106,8 +106,9 @@ static void magic_for(int d, uint32_t* m, int32_t* L) {
 // max(longest item, sum of item times / kSlots).  The planner picks, per tenant, the (tile, split) option
 // that minimises that maximum over the whole launch.
 static const double kFirstCost = 3000.0;
-static const double kStepCost[kNumTileCfgs] = {1620.0, 1150.0, 1110.0, 750.0, 640.0, 650.0};
-static const double kEpiCost[kNumTileCfgs] = {5900.0, 3650.0, 4000.0, 2160.0, 1170.0, 680.0};
+static const double kStepCost[kNumTileCfgs] = {1620.0, 1150.0, 1110.0, 750.0, 640.0, 650.0, 300.0};
+static const double kEpiCost[kNumTileCfgs] = {5900.0, 3650.0, 4000.0, 2160.0, 1170.0, 680.0, 3650.0};
+static const double kRowStageCost = 2500.0;     // row tile: copying image rows and filters into LDS
 static const double kGenericStepFactor = 4.5;   // element-wise gathers are bound by the texture addresser
 static const double kSplitCost = 6500.0, kSplitRoundCost = 2700.0;
 static const int kSlots = 2 * kNumCUs;          // two workgroups resident per compute unit
@@ -118,6 +119,34 @@ struct Option {
   int64_t items;
   double item_time, area;
 };
+
+// Row tile eligibility (see conv_tile_rows): 16-bit types, S*C <= 32, image rows a multiple of 16 bytes,
+// stride*C even, LDS footprint within the allocation.
+static bool row_tile_ok(const st_conv_desc& d) {
+  if (d.in_dtype == ST_DT_F32) return false;
+  if (d.C % 8 == 0) return false;                       // the vector kernels are better
+  if (d.S * d.C > 32) return false;
+  if ((d.W * d.C * 2) % 16 != 0) return false;
+  if ((d.stride * d.C * 2) % 4 != 0) return false;       // pixel patches must stay 4-byte aligned in LDS
+  const int lpad = d.pad * d.C * 2;
+  const int pitch = ((lpad + d.W * d.C * 2 + lpad + 15) & ~15) + 64;
+  const int Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
+  const int reach = (Q - 1) * d.stride * d.C * 2 + 64;             // furthest byte a pixel operand read touches
+  if (reach > pitch) return false;
+  return (int64_t)d.R * pitch + (int64_t)kTileShapes[kRowCfg].NT * d.R * 64 <= kSmemBytes;
+}
+
+static Option make_row_option(const st_conv_desc& d) {
+  Option o;
+  const int P = (d.H + 2 * d.pad - d.R) / d.stride + 1, Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
+  o.cfg = kRowCfg;
+  o.split = 1;
+  o.steps_per_split = d.R;
+  o.items = (int64_t)d.N * P * cdiv(Q, kTileShapes[kRowCfg].MT) * cdiv(d.K, kTileShapes[kRowCfg].NT);
+  o.item_time = kFirstCost + kRowStageCost + d.R * kStepCost[kRowCfg] + kEpiCost[kRowCfg];
+  o.area = o.item_time * (double)o.items;
+  return o;
+}
 
 static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, int cfg, int split) {
   Option o;
@@ -136,12 +165,20 @@ static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, in
   return o;
 }
 
-static std::vector<Option> tenant_options(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, const st_plan_opts& o) {
+static std::vector<Option> tenant_options(const st_conv_desc& d, int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok,
+                                          const st_plan_opts& o) {
   std::vector<Option> out;
+  const bool row_ok = row_tile_ok(d);
+  if (row_ok && (o.tile_cfg == 0 || o.tile_cfg - 1 == kRowCfg) && o.split_k <= 1) {
+    out.push_back(make_row_option(d));
+    if (o.tile_cfg - 1 == kRowCfg) return out;
+  }
   for (int c = 0; c < kNumTileCfgs; ++c) {
+    if (c == kRowCfg) continue;
     if (!vec_ok && !kGenericCfg[c]) continue;
     if (o.tile_cfg > 0) {
       int forced = o.tile_cfg - 1;
+      if (forced == kRowCfg) forced = 1;                 // row tile requested but not eligible
       if (!vec_ok && !kGenericCfg[forced]) forced = (kTileShapes[forced].MT >= 128) ? 1 : 3;  // nearest gather kernel
       if (c != forced) continue;
     }
@@ -297,7 +334,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
     for (int t = 0; t < n_tenants; ++t) {
       const st_tenant_info& ti = p->info[t];
       const bool vec_ok = descs[t].C % (16 / elem_size(descs[t].in_dtype)) == 0;
-      options[t] = tenant_options(ti.M, ti.Ngemm, ti.Kgemm * elem_size(descs[t].in_dtype), vec_ok, o);
+      options[t] = tenant_options(descs[t], ti.M, ti.Ngemm, ti.Kgemm * elem_size(descs[t].in_dtype), vec_ok, o);
     }
     std::vector<int> pick;
     choose_all(options, o.target_items > 0 ? o.target_items : kSlots, &pick);
@@ -310,6 +347,11 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       ti.MT = kTileShapes[op.cfg].MT;
       ti.NT = kTileShapes[op.cfg].NT;
       ti.tiles_m = cdiv(ti.M, ti.MT);
+      ti.row_tiled = (op.cfg == kRowCfg) ? 1 : 0;
+      if (ti.row_tiled) {
+        ti.k_steps = descs[t].R;
+        ti.tiles_m = descs[t].N * ti.P * cdiv(ti.Q, ti.MT);
+      }
       ti.tiles_n = cdiv(ti.Ngemm, ti.NT);
       ti.split_k = op.split;
       ti.k_steps_per_split = op.steps_per_split;
@@ -365,8 +407,11 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0) ? 1 : 0;
       magic_for(d.C, &T.magic_c, &T.shift_c);
       magic_for(d.S, &T.magic_s, &T.shift_s);
+      magic_for(d.S * d.C, &T.magic_sc, &T.shift_sc);
+      magic_for((int)std::min<int64_t>(ti.Kgemm, (1 << 20) - 1), &T.magic_kg, &T.shift_kg);
       T.x_bytes = (uint32_t)((int64_t)d.N * d.C * d.H * d.W * elem_size(d.in_dtype));
       T.w_bytes = (uint32_t)(ti.Ngemm * ti.Kgemm * elem_size(d.in_dtype));
+      T.y_bytes = (uint32_t)(ti.M * ti.Ngemm * elem_size(d.out_dtype));
     }
   } catch (const std::bad_alloc&) {
     delete p;

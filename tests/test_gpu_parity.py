@@ -33,6 +33,9 @@ SMALL = [
     ConvShape(2, 12, 9, 9, 36, 3, 3, 1, 1, "f32", "f32"),
     ConvShape(1, 5, 8, 9, 7, 3, 3, 2, 2, "f32", "f32"),          # odd everything, scalar stores
     ConvShape(1, 40, 6, 6, 30, 1, 1, 2, 0, "bf16", "bf16"),
+    ConvShape(2, 3, 20, 32, 40, 7, 7, 2, 3, "bf16", "f32"),     # row tile (few channels), ragged filters
+    ConvShape(1, 3, 9, 272, 72, 7, 7, 2, 3, "bf16", "bf16"),    # row tile, two pixel tiles per output row
+    ConvShape(1, 4, 9, 16, 24, 3, 7, 1, 3, "f16", "f32"),       # row tile, stride 1, C = 4
 ]
 
 
@@ -46,7 +49,7 @@ def _run_small(torch, helpers, **opts):
     return tenants, plan
 
 
-@pytest.mark.parametrize("tile_cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("tile_cfg", [1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("split_k", [1, 3])
 def test_every_tile_shape_and_split(torch, tile_cfg, split_k):
     from tests import helpers

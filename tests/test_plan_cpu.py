@@ -66,7 +66,11 @@ def _expected_tenant_major(plan, n_tenants):
         ti = sc.st_conv_plan_tenant_info(plan, t)
         mt, nt, kb = sc.st_tile_shape(ti.tile_cfg)
         assert (mt, nt) == (ti.MT, ti.NT)
-        assert ti.tiles_m == -(-ti.M // mt) and ti.tiles_n == -(-ti.Ngemm // nt)
+        if ti.row_tiled:       # pixel tiles are segments of single output rows
+            assert ti.tiles_m == (ti.M // (ti.P * ti.Q)) * ti.P * -(-ti.Q // mt) and ti.split_k == 1
+        else:
+            assert ti.tiles_m == -(-ti.M // mt)
+        assert ti.tiles_n == -(-ti.Ngemm // nt)
         assert ti.k_steps_per_split == -(-ti.k_steps // ti.split_k)
         assert (ti.split_k - 1) * ti.k_steps_per_split < ti.k_steps, "an empty K slice"
         assert ti.item_begin == len(rows) and ti.item_count == ti.tiles_m * ti.tiles_n * ti.split_k
@@ -100,6 +104,9 @@ def test_work_lists_bit_exact(cfg, opts):
         ti = sc.st_conv_plan_tenant_info(p, t)
         kb = sc.st_tile_shape(ti.tile_cfg)[2]
         es = 4 if s.dtype == "f32" else 2
+        if ti.row_tiled:
+            assert ti.k_steps == s.R      # one filter row per step
+            continue
         assert ti.k_steps == -(-ti.Kgemm * es // kb)
         covered = 0
         for i in range(ti.split_k):
@@ -126,6 +133,15 @@ def test_fused_order_longest_first():
     for cfg in set(c for _, c in steps):
         seq = [s for s, c in steps if c == cfg]
         assert seq == sorted(seq, reverse=True)
+
+
+def test_row_tile_is_chosen_for_the_stem_only_when_eligible():
+    stem = synth.ConvShape(1, 3, 224, 224, 64, 7, 7, 2, 3)
+    p = _host_plan([stem, synth.ConvShape(1, 3, 30, 26, 64, 7, 7, 2, 3), synth.ConvShape(1, 64, 56, 56, 64, 3, 3, 1, 1)])
+    a, b, c = (sc.st_conv_plan_tenant_info(p, t) for t in range(3))
+    assert a.row_tiled == 1 and (a.MT, a.NT) == (128, 64) and a.tiles_m == 112 and a.k_steps == 7
+    assert b.row_tiled == 0      # image rows are not a multiple of 16 bytes: element-wise gather kernel
+    assert c.row_tiled == 0
 
 
 def test_tile_family_is_sane():
