@@ -820,21 +820,29 @@ __global__ __launch_bounds__(kThreads, 2) void st_conv_kernel(const TenantDev* _
 
 __global__ void st_empty_kernel() {}
 
-// NHWC max-pool, one thread per output element; padding never wins.
-template <int DT>
+// NHWC max-pool; padding never wins.  One thread per (output pixel, group of VEC channels): the window's
+// 16-byte channel vectors are loaded whole.  VEC = 1 is the fallback for channel counts that are not a
+// multiple of the vector width.
+template <int DT, int VEC>
 __global__ __launch_bounds__(256) void st_maxpool_kernel(const void* __restrict__ xv, void* __restrict__ yv, int N, int H,
                                                          int W, int C, int P, int Q, int win, int stride, int pad) {
-  const int64_t total = (int64_t)N * P * Q * C;
+  constexpr int ES = (DT == ST_DT_F32) ? 4 : 2;
+  const int CV = C / VEC;
+  const int64_t total = (int64_t)N * P * Q * CV;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int c = (int)(idx % C);
-  int64_t t = idx / C;
+  const int cv = (int)(idx % CV);
+  int64_t t = idx / CV;
   const int q = (int)(t % Q);
   t /= Q;
   const int p = (int)(t % P);
   const int n = (int)(t / P);
-  float best = -__builtin_inff();
-  uint32_t best_bits = 0u;
+  float best[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) best[e] = -__builtin_inff();
+  uint32_t bits[VEC];      // bit pattern of the current maximum, so the result is copied, not re-rounded
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) bits[e] = 0u;
   bool any = false;
   for (int r = 0; r < win; ++r) {
     const int h = p * stride - pad + r;
@@ -842,21 +850,43 @@ __global__ __launch_bounds__(256) void st_maxpool_kernel(const void* __restrict_
     for (int s = 0; s < win; ++s) {
       const int w = q * stride - pad + s;
       if ((unsigned)w >= (unsigned)W) continue;
-      const int64_t o = (((int64_t)n * H + h) * W + w) * C + c;
-      float v;
-      uint32_t bits;
-      if (DT == ST_DT_F32) {
-        v = ((const float*)xv)[o];
-        bits = __builtin_bit_cast(uint32_t, v);
+      const char* src = (const char*)xv + ((((int64_t)n * H + h) * W + w) * C + (int64_t)cv * VEC) * ES;
+      uint32_t raw[VEC * ES / 4 > 0 ? VEC * ES / 4 : 1];
+      if constexpr (VEC * ES == 16) {
+        const u32x4 v = *(const u32x4*)src;
+        raw[0] = v[0]; raw[1] = v[1]; raw[2] = v[2]; raw[3] = v[3];
+      } else if constexpr (ES == 4) {
+        raw[0] = *(const uint32_t*)src;
       } else {
-        bits = ((const uint16_t*)xv)[o];
-        v = (DT == ST_DT_BF16) ? bf16_bits_to_f32((uint16_t)bits) : f16_bits_to_f32((uint16_t)bits);
+        raw[0] = *(const uint16_t*)src;
       }
-      if (!any || v > best) { best = v; best_bits = bits; any = true; }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        uint32_t b;
+        float v;
+        if constexpr (ES == 4) {
+          b = raw[e];
+          v = __builtin_bit_cast(float, b);
+        } else {
+          b = (raw[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+          v = (DT == ST_DT_BF16) ? bf16_bits_to_f32((uint16_t)b) : f16_bits_to_f32((uint16_t)b);
+        }
+        if (!any || v > best[e]) { best[e] = v; bits[e] = b; }
+      }
+      any = true;
     }
   }
-  if (DT == ST_DT_F32) ((uint32_t*)yv)[idx] = best_bits;
-  else ((uint16_t*)yv)[idx] = (uint16_t)best_bits;
+  char* dst = (char*)yv + idx * (int64_t)(VEC * ES);
+  if constexpr (VEC * ES == 16) {
+    u32x4 o;
+    if constexpr (ES == 4) { o = u32x4{bits[0], bits[1], bits[2], bits[3]}; }
+    else { o = u32x4{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)}; }
+    *(u32x4*)dst = o;
+  } else if constexpr (ES == 4) {
+    *(uint32_t*)dst = bits[0];
+  } else {
+    *(uint16_t*)dst = (uint16_t)bits[0];
+  }
 }
 
 int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
@@ -887,16 +917,18 @@ int launch_empty(void* stream) {
 
 int launch_maxpool(const void* x, void* y, int N, int H, int W, int C, int P, int Q, int win, int stride, int pad,
                    int dtype, void* stream) {
-  const int64_t total = (int64_t)N * P * Q * C;
+  hipStream_t s = (hipStream_t)stream;
+  const int es = dtype == ST_DT_F32 ? 4 : 2;
+  const int vec = (C % (16 / es) == 0) ? 16 / es : 1;
+  const int64_t total = (int64_t)N * P * Q * (C / vec);
   if (total <= 0) return 0;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipStream_t s = (hipStream_t)stream;
-  if (dtype == ST_DT_F32)
-    hipLaunchKernelGGL(st_maxpool_kernel<ST_DT_F32>, dim3(blocks), dim3(256), 0, s, x, y, N, H, W, C, P, Q, win, stride, pad);
-  else if (dtype == ST_DT_BF16)
-    hipLaunchKernelGGL(st_maxpool_kernel<ST_DT_BF16>, dim3(blocks), dim3(256), 0, s, x, y, N, H, W, C, P, Q, win, stride, pad);
-  else
-    hipLaunchKernelGGL(st_maxpool_kernel<ST_DT_F16>, dim3(blocks), dim3(256), 0, s, x, y, N, H, W, C, P, Q, win, stride, pad);
+#define ST_POOL(DT, V) \
+  hipLaunchKernelGGL((st_maxpool_kernel<DT, V>), dim3(blocks), dim3(256), 0, s, x, y, N, H, W, C, P, Q, win, stride, pad)
+  if (dtype == ST_DT_F32) { if (vec == 4) ST_POOL(ST_DT_F32, 4); else ST_POOL(ST_DT_F32, 1); }
+  else if (dtype == ST_DT_BF16) { if (vec == 8) ST_POOL(ST_DT_BF16, 8); else ST_POOL(ST_DT_BF16, 1); }
+  else { if (vec == 8) ST_POOL(ST_DT_F16, 8); else ST_POOL(ST_DT_F16, 1); }
+#undef ST_POOL
   return (int)hipGetLastError();
 }
 

@@ -162,12 +162,13 @@ def test_rebind_and_empty_plan(torch):
     helpers.check_tenant(b, "after rebind")
 
 
-def test_maxpool(torch):
+@pytest.mark.parametrize("C,dtype", [(24, "bf16"), (5, "bf16"), (16, "f16"), (12, "f32"), (3, "f32")])
+def test_maxpool(torch, C, dtype):
     from oracle import oracle
     from tests import helpers
-    x = synth.to_storage(synth.uniform_pm1(synth.stream_state(92, 0, 0, 1), 2 * 24 * 15 * 14), "bf16").reshape(2, 24, 15, 14)
-    dx = helpers.to_device_nhwc(x, "bf16")
-    dy = torch.zeros((2, 8, 7, 24), dtype=torch.bfloat16, device="cuda")
-    sc.st_maxpool_nhwc(dx, dy, 2, 15, 14, 24, 3, 2, 1, "bf16")
+    x = synth.to_storage(synth.uniform_pm1(synth.stream_state(92, C, 0, 1), 2 * C * 15 * 14), dtype).reshape(2, C, 15, 14)
+    dx = helpers.to_device_nhwc(x, dtype)
+    dy = torch.zeros((2, 8, 7, C), dtype=helpers.torch_dtype(dtype), device="cuda")
+    sc.st_maxpool_nhwc(dx, dy, 2, 15, 14, C, 3, 2, 1, dtype)
     _sync(torch)
     assert np.array_equal(helpers.from_device_nhwc(dy), oracle.maxpool2d(x, 3, 2, 1))
