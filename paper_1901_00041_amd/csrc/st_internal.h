@@ -25,8 +25,8 @@ constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {128, 64, 2, 2, 32, 128, 2},   // 1: wave tile 64x32
     {64, 128, 2, 2, 32, 128, 2},   // 2: wave tile 32x64
     {64, 64, 2, 2, 32, 128, 4},    // 3: wave tile 32x32
-    {32, 64, 2, 2, 16, 128, 4},    // 4: wave tile 16x32
-    {16, 64, 1, 4, 16, 128, 4},    // 5: wave tile 16x16
+    {32, 64, 2, 2, 16, 256, 2},    // 4: wave tile 16x32
+    {16, 64, 1, 4, 16, 256, 2},    // 5: wave tile 16x16
     {128, 64, 2, 2, 32, 64, 2},    // 6: row tile (few input channels), wave tile 64x32
 };
 constexpr int smem_need(int c) { return 2 * (kTileShapes[c].MT + kTileShapes[c].NT) * (kTileShapes[c].KB + 16); }

@@ -182,76 +182,84 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
     if (T.out_dtype == ST_DT_F32) {
       constexpr int NV = NT / 4;
       constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
-      f32x4 a[IT];
-      uint32_t off[IT];
+      constexpr int UB = IT < 4 ? IT : 4;        // vectors in flight per thread (bounds register use)
 #pragma unroll
-      for (int u = 0; u < IT; ++u) {
-        const int v = u * kThreads + tid;
-        const int row = v / NV, cv = v % NV;
-        const int m = m0 + row, ch = n0 + cv * 4;
-        const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
-        off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset;
-        a[u] = *(const f32x4*)(sC + (row < MT ? row : 0) * PITCH + cv * 4);
-      }
-      if (has_res) {
+      for (int u0 = 0; u0 < IT; u0 += UB) {
+        f32x4 a[UB];
+        uint32_t off[UB];
 #pragma unroll
-        for (int u = 0; u < IT; ++u) a[u] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
-      }
-#pragma unroll
-      for (int u = 0; u < IT; ++u) {
-        if (relu) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a[u][e] = a[u][e] > 0.f ? a[u][e] : 0.f;
+        for (int u = 0; u < UB; ++u) {
+          const int v = (u0 + u) * kThreads + tid;
+          const int row = v / NV, cv = v % NV;
+          const int m = m0 + row, ch = n0 + cv * 4;
+          const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+          off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset;
+          a[u] = *(const f32x4*)(sC + (row < MT ? row : 0) * PITCH + cv * 4);
         }
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a[u]), ry, (int)off[u], 0, 0);
+        if (has_res) {
+#pragma unroll
+          for (int u = 0; u < UB; ++u) a[u] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          if (relu) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[u][e] = a[u][e] > 0.f ? a[u][e] : 0.f;
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a[u]), ry, (int)off[u], 0, 0);
+        }
       }
     } else {
       constexpr int NV = NT / 8;
       constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+      constexpr int UB = IT < 4 ? IT : 4;
       const bool isbf = (T.out_dtype == ST_DT_BF16);
-      f32x4 lo[IT], hi[IT];
-      uint32_t off[IT];
 #pragma unroll
-      for (int u = 0; u < IT; ++u) {
-        const int v = u * kThreads + tid;
-        const int row = v / NV, cv = v % NV;
-        const int m = m0 + row, ch = n0 + cv * 8;
-        const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
-        off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
-        const float* src = sC + (row < MT ? row : 0) * PITCH + cv * 8;
-        lo[u] = *(const f32x4*)src;
-        hi[u] = *(const f32x4*)(src + 4);
-      }
-      if (has_res) {
+      for (int u0 = 0; u0 < IT; u0 += UB) {
+        f32x4 lo[UB], hi[UB];
+        uint32_t off[UB];
 #pragma unroll
-        for (int u = 0; u < IT; ++u) {
-          const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
+        for (int u = 0; u < UB; ++u) {
+          const int v = (u0 + u) * kThreads + tid;
+          const int row = v / NV, cv = v % NV;
+          const int m = m0 + row, ch = n0 + cv * 8;
+          const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+          off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
+          const float* src = sC + (row < MT ? row : 0) * PITCH + cv * 8;
+          lo[u] = *(const f32x4*)src;
+          hi[u] = *(const f32x4*)(src + 4);
+        }
+        if (has_res) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint16_t h0 = (uint16_t)(r[e >> 1] >> (16 * (e & 1))), h1 = (uint16_t)(r[2 + (e >> 1)] >> (16 * (e & 1)));
-            lo[u][e] += isbf ? bf16_bits_to_f32(h0) : f16_bits_to_f32(h0);
-            hi[u][e] += isbf ? bf16_bits_to_f32(h1) : f16_bits_to_f32(h1);
+          for (int u = 0; u < UB; ++u) {
+            const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const uint16_t h0 = (uint16_t)(r[e >> 1] >> (16 * (e & 1))), h1 = (uint16_t)(r[2 + (e >> 1)] >> (16 * (e & 1)));
+              lo[u][e] += isbf ? bf16_bits_to_f32(h0) : f16_bits_to_f32(h0);
+              hi[u][e] += isbf ? bf16_bits_to_f32(h1) : f16_bits_to_f32(h1);
+            }
           }
         }
-      }
 #pragma unroll
-      for (int u = 0; u < IT; ++u) {
-        if (relu) {
+        for (int u = 0; u < UB; ++u) {
+          if (relu) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            lo[u][e] = lo[u][e] > 0.f ? lo[u][e] : 0.f;
-            hi[u][e] = hi[u][e] > 0.f ? hi[u][e] : 0.f;
+            for (int e = 0; e < 4; ++e) {
+              lo[u][e] = lo[u][e] > 0.f ? lo[u][e] : 0.f;
+              hi[u][e] = hi[u][e] > 0.f ? hi[u][e] : 0.f;
+            }
           }
-        }
-        u32x4 pk;
+          u32x4 pk;
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          pk[e] = isbf ? ((uint32_t)f32_to_bf16_rne(lo[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(lo[u][2 * e + 1]) << 16))
-                       : ((uint32_t)f32_to_f16_bits(lo[u][2 * e]) | ((uint32_t)f32_to_f16_bits(lo[u][2 * e + 1]) << 16));
-          pk[2 + e] = isbf ? ((uint32_t)f32_to_bf16_rne(hi[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(hi[u][2 * e + 1]) << 16))
-                           : ((uint32_t)f32_to_f16_bits(hi[u][2 * e]) | ((uint32_t)f32_to_f16_bits(hi[u][2 * e + 1]) << 16));
+          for (int e = 0; e < 2; ++e) {
+            pk[e] = isbf ? ((uint32_t)f32_to_bf16_rne(lo[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(lo[u][2 * e + 1]) << 16))
+                         : ((uint32_t)f32_to_f16_bits(lo[u][2 * e]) | ((uint32_t)f32_to_f16_bits(lo[u][2 * e + 1]) << 16));
+            pk[2 + e] = isbf ? ((uint32_t)f32_to_bf16_rne(hi[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(hi[u][2 * e + 1]) << 16))
+                             : ((uint32_t)f32_to_f16_bits(hi[u][2 * e]) | ((uint32_t)f32_to_f16_bits(hi[u][2 * e + 1]) << 16));
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(pk, ry, (int)off[u], 0, 0);
         }
-        __builtin_amdgcn_raw_buffer_store_b128(pk, ry, (int)off[u], 0, 0);
       }
     }
   } else {
@@ -559,7 +567,7 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
     // device-coherent reads, each a trip to memory, overlap; slices past split_k read as zero.
     constexpr int NGRP = BM * BN * NG;
     constexpr int GB = NGRP < 4 ? NGRP : 4;
-    constexpr int SB = 8;
+    constexpr int SB = (NGRP > 4) ? 4 : 8;   // at most 32 partial vectors (128 registers) in flight
     static_assert(NGRP % GB == 0, "group batching");
     const int split = T.split_k;
 #pragma unroll

@@ -106,12 +106,13 @@ static void magic_for(int d, uint32_t* m, int32_t* L) {
 // max(longest item, sum of item times / kSlots).  The planner picks, per tenant, the (tile, split) option
 // that minimises that maximum over the whole launch.
 static const double kFirstCost = 3000.0;
-static const double kStepCost[kNumTileCfgs] = {1620.0, 1150.0, 1110.0, 750.0, 640.0, 650.0, 300.0};
-static const double kEpiCost[kNumTileCfgs] = {5900.0, 3650.0, 4000.0, 2160.0, 1170.0, 680.0, 3650.0};
-static const double kRowStageCost = 2500.0;     // row tile: copying image rows and filters into LDS
+static const double kStepCost[kNumTileCfgs] = {1770.0, 1240.0, 1180.0, 750.0, 1180.0, 890.0, 520.0};
+static const double kEpiCost[kNumTileCfgs] = {5200.0, 3000.0, 3100.0, 2000.0, 1200.0, 1100.0, 2800.0};
+static const double kRowStageCost = 6500.0;     // row tile: copying image rows and filters into LDS
 static const double kGenericStepFactor = 4.5;   // element-wise gathers are bound by the texture addresser
-static const double kSplitCost = 6500.0, kSplitRoundCost = 2700.0;
-static const int kSlots = 2 * kNumCUs;          // two workgroups resident per compute unit
+static const double kSplitCost = 5000.0, kSplitPerElem = 1.0, kSplitRoundCost = 2700.0;   // hand-off grows with the tile
+static const int kSlots = 400;                  // two workgroups resident per compute unit (512), derated because
+                                                // co-resident workgroups share one LDS pipe
 static const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
 
 struct Option {
@@ -160,7 +161,8 @@ static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, in
   o.items = (int64_t)cdiv(M, kTileShapes[cfg].MT) * cdiv(Ng, kTileShapes[cfg].NT) * split;
   const double step = kStepCost[cfg] * (vec_ok ? 1.0 : kGenericStepFactor);
   o.item_time = kFirstCost + per * step + kEpiCost[cfg] +
-                (split > 1 ? kSplitCost + kSplitRoundCost * ((split - 1) / 8) : 0.0);
+                (split > 1 ? kSplitCost + kSplitPerElem * kTileShapes[cfg].MT * kTileShapes[cfg].NT +
+                                 kSplitRoundCost * ((split - 1) / 8) : 0.0);
   o.area = o.item_time * (double)o.items;
   return o;
 }
