@@ -92,14 +92,14 @@ typedef struct st_tenant_info {
   int64_t bytes;               /* x + w + y, each element once                              */
   int32_t tile_cfg;            /* index into st_tile_shape()                                */
   int32_t MT, NT;              /* pixels and filters per tile                               */
-  int32_t tiles_m, tiles_n;    /* tiles_m = ceil(M/MT), or N*P*ceil(Q/MT) when row_tiled          */
+  int32_t tiles_m, tiles_n;    /* tiles_m = ceil(M/MT), or N*ceil(P/rows_per_tile)*ceil(Q/MT) when row_tiled */
   int32_t split_k;             /* slices of Kgemm per output tile                           */
   int32_t k_steps;             /* K steps (of the tile shape's k_step_bytes per row) over Kgemm */
   int32_t k_steps_per_split;   /* ceil(k_steps / split_k); the last slice may be shorter    */
   int64_t item_begin;          /* slice [item_begin, item_begin+item_count) of the          */
   int64_t item_count;          /*   tenant-major work list belongs to this tenant           */
-  int32_t row_tiled;           /* 1: pixel tiles are segments of single output rows         */
-  int32_t reserved;
+  int32_t row_tiled;           /* 1: pixel tiles are row segments of consecutive output rows */
+  int32_t rows_per_tile;       /* output rows per tile when row_tiled, else 0                */
 } st_tenant_info;
 
 typedef struct st_plan_info {

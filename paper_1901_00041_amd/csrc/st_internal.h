@@ -18,8 +18,9 @@ struct TileShape {
   int MT, NT, WPX, WCH, MF, KB, D;
 };
 constexpr int kNumTileCfgs = 7;
-constexpr int kRowCfg = 6;         // the row tile for few-channel layers (conv_tile_rows): 128 pixels of one
-                                   // output row x 64 filters, one filter row (r) per K step
+constexpr int kRowCfg = 6;         // the row tile for few-channel layers (conv_tile_rows): 128-pixel segments of
+                                   // kRowsPerTile consecutive output rows x 64 filters, one filter row per K step
+constexpr int kRowsPerTile = 4;    // most output rows one row-tile work item may take (the planner picks 1, 2 or 4)
 constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {128, 128, 2, 2, 32, 128, 2},  // 0: wave tile 64x64
     {128, 64, 2, 2, 32, 128, 2},   // 1: wave tile 64x32
@@ -55,7 +56,8 @@ struct TenantDev {
   int32_t shift_sc, shift_kg;   // same for d = S*C and d = Kgemm (row tile only)
   uint32_t magic_sc, magic_kg;
   uint32_t x_bytes, w_bytes;  // buffer sizes for bounds-checked loads
-  uint32_t y_bytes, pad_;     // size of y (and of the residual) in bytes
+  uint32_t y_bytes;           // size of y (and of the residual) in bytes
+  int32_t rows_per_tile;      // row tile only: output rows per work item
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 

@@ -148,7 +148,9 @@ constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every bu
 // ---- epilogue shared by all tile kernels: (+ residual) -> ReLU -> cast -> store ---------------------
 // acc[i][j] is the MF x MF block at pixels wm0 + i*MF, filters wn0 + j*MF of the tile whose first pixel is
 // im2col row m0 and first filter n0; rows at or past m_end are not stored.
-template <int MT, int NT, int BM, int BN, int MF, class Acc>
+// The transposition buffer `smem` holds MT/PASSES pixel rows; with PASSES > 1 the tile is written out in
+// that many slices of consecutive pixel rows.
+template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, class Acc>
 __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
                                               int wn0, int lrow, int lk, int tid, char* smem, uint64_t* prof = nullptr) {
   constexpr int NG = (MF == 32) ? 4 : 1;
@@ -160,28 +162,34 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
     // Transpose through LDS: accumulators go to an fp32 [pixel][filter] tile, then every lane handles 16
     // bytes of one output row, so residual loads and output stores are whole contiguous rows.
     constexpr int PITCH = NT + 4;   // floats; the pad keeps the 16-byte writes of 16 pixels on distinct banks
-    static_assert(MT * PITCH * 4 <= kSmemBytes, "output tile does not fit the LDS allocation");
+    constexpr int MP = MT / PASSES; // pixel rows per slice
+    static_assert(MT % PASSES == 0 && MP % MF == 0, "slices must hold whole MFMA blocks");
+    static_assert(MP * PITCH * 4 <= kSmemBytes, "output tile does not fit the LDS allocation");
     float* sC = (float*)smem;
-    __syncthreads();                // operand buffers (and the split-K flag) are no longer read
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(has_res ? T.res : T.y, T.y_bytes);
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+    const int mp0 = m0 + pass * MP;   // first im2col row of this slice
+    __syncthreads();                // the buffer (operands, split-K flag, or the previous slice) is no longer read
 #pragma unroll
     for (int i = 0; i < BM; ++i)
 #pragma unroll
       for (int j = 0; j < BN; ++j)
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
-          const int row = wm0 + i * MF + lrow;
+          const int row = wm0 + i * MF + lrow - pass * MP;
           const int chl = wn0 + j * MF + ((MF == 32) ? (8 * g + 4 * lk) : (4 * lk));
-          *(f32x4*)(sC + row * PITCH + chl) = f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          if (PASSES == 1 || (row >= 0 && row < MP))
+            *(f32x4*)(sC + row * PITCH + chl) = f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
         }
     __syncthreads();
     if (prof && tid == 0) prof[7] = __builtin_readcyclecounter();
     // Branch-free read-back: rows past the tile end or filters past K get an out-of-range offset, which
     // drops the store (and makes the residual load return zero).
-    const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
-    const __amdgpu_buffer_rsrc_t rr = make_rsrc(has_res ? T.res : T.y, T.y_bytes);
     if (T.out_dtype == ST_DT_F32) {
       constexpr int NV = NT / 4;
-      constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+      constexpr int IT = (MP * NV + kThreads - 1) / kThreads;
       constexpr int UB = IT < 4 ? IT : 4;        // vectors in flight per thread (bounds register use)
 #pragma unroll
       for (int u0 = 0; u0 < IT; u0 += UB) {
@@ -191,10 +199,10 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
         for (int u = 0; u < UB; ++u) {
           const int v = (u0 + u) * kThreads + tid;
           const int row = v / NV, cv = v % NV;
-          const int m = m0 + row, ch = n0 + cv * 4;
-          const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+          const int m = mp0 + row, ch = n0 + cv * 4;
+          const bool ok = (MP * NV % kThreads == 0 || v < MP * NV) & (m < m_end) & (ch < Kf);
           off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset;
-          a[u] = *(const f32x4*)(sC + (row < MT ? row : 0) * PITCH + cv * 4);
+          a[u] = *(const f32x4*)(sC + (row < MP ? row : 0) * PITCH + cv * 4);
         }
         if (has_res) {
 #pragma unroll
@@ -211,7 +219,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
       }
     } else {
       constexpr int NV = NT / 8;
-      constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+      constexpr int IT = (MP * NV + kThreads - 1) / kThreads;
       constexpr int UB = IT < 4 ? IT : 4;
       const bool isbf = (T.out_dtype == ST_DT_BF16);
 #pragma unroll
@@ -222,10 +230,10 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
         for (int u = 0; u < UB; ++u) {
           const int v = (u0 + u) * kThreads + tid;
           const int row = v / NV, cv = v % NV;
-          const int m = m0 + row, ch = n0 + cv * 8;
-          const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+          const int m = mp0 + row, ch = n0 + cv * 8;
+          const bool ok = (MP * NV % kThreads == 0 || v < MP * NV) & (m < m_end) & (ch < Kf);
           off[u] = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
-          const float* src = sC + (row < MT ? row : 0) * PITCH + cv * 8;
+          const float* src = sC + (row < MP ? row : 0) * PITCH + cv * 8;
           lo[u] = *(const f32x4*)src;
           hi[u] = *(const f32x4*)(src + 4);
         }
@@ -262,6 +270,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
         }
       }
     }
+    }   // slices
   } else {
   #pragma unroll
     for (int i = 0; i < BM; ++i) {
@@ -280,22 +289,30 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
             float* y = (float*)T.y + o;
             if (has_res) {
               const float* rp = (const float*)T.res + o;
-              for (int e = 0; e < nv; ++e) v[e] += rp[e];
+_Pragma("unroll")
+              for (int e = 0; e < 4; ++e) if (e < nv) v[e] += rp[e];
             }
             if (relu)
+_Pragma("unroll")
               for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
             if (vec4) *(f32x4*)y = f32x4{v[0], v[1], v[2], v[3]};
-            else for (int e = 0; e < nv; ++e) y[e] = v[e];
+            else {
+_Pragma("unroll")
+              for (int e = 0; e < 4; ++e) if (e < nv) y[e] = v[e];
+            }
           } else {
             uint16_t* y = (uint16_t*)T.y + o;
             const bool isbf = (T.out_dtype == ST_DT_BF16);
             if (has_res) {
               const uint16_t* rp = (const uint16_t*)T.res + o;
-              for (int e = 0; e < nv; ++e) v[e] += isbf ? bf16_bits_to_f32(rp[e]) : f16_bits_to_f32(rp[e]);
+_Pragma("unroll")
+              for (int e = 0; e < 4; ++e) if (e < nv) v[e] += isbf ? bf16_bits_to_f32(rp[e]) : f16_bits_to_f32(rp[e]);
             }
             if (relu)
+_Pragma("unroll")
               for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
             uint16_t hbits[4];
+_Pragma("unroll")
             for (int e = 0; e < 4; ++e) hbits[e] = isbf ? f32_to_bf16_rne(v[e]) : f32_to_f16_bits(v[e]);
             if (vec4) {
               uint2 pk;
@@ -303,7 +320,8 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
               pk.y = (uint32_t)hbits[2] | ((uint32_t)hbits[3] << 16);
               *(uint2*)y = pk;
             } else {
-              for (int e = 0; e < nv; ++e) y[e] = hbits[e];
+_Pragma("unroll")
+              for (int e = 0; e < 4; ++e) if (e < nv) y[e] = hbits[e];
             }
           }
         }
@@ -611,15 +629,18 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
 // ---- row tile for layers with very few input channels ---------------------------------------------
 // For the 7x7 / stride-2 / 3-channel stem the im2col row of one (pixel, filter row r) is S*C = 21
 // contiguous elements of the NHWC image, at an odd element offset, so neither 16-byte gathers nor the
-// element-wise gather variant are efficient.  This kernel takes one output row segment (up to 128 pixels)
-// x 64 filters per workgroup: the R input rows it needs are copied whole into LDS with aligned 16-byte
-// loads (rows outside the image and the left/right padding are zeros), the 64 filters are copied into
-// an LDS array [filter][r][32] padded with zeros, and the MFMA operands are assembled from LDS, the pixel
-// side with 2-byte reads.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by the planner:
-// 16-bit types, S*C <= 32, W*C*2 a multiple of 16, LDS footprint within the allocation.
+// element-wise gather variant are efficient.  This kernel gives one workgroup kRowsPerTile consecutive
+// output rows (a segment of up to 128 pixels of each) x 64 filters: the input rows they need are copied
+// whole into LDS with aligned 16-byte loads (rows outside the image and the left/right padding are
+// zeros), the 64 filters are copied once into an LDS array [filter][r][32] padded with zeros, and the
+// MFMA operands are assembled from LDS.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by
+// the planner: 16-bit types, S*C <= 32, W*C*2 a multiple of 16, stride*C even, LDS footprint.
 template <int DT>
 __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
+  const int RT = T.rows_per_tile;                    // output rows per work item (1..kRowsPerTile)
+  constexpr int EPI_PASSES = 2;
+  constexpr int kStageBytes = (MT / EPI_PASSES) * (NT + 4) * 4;      // epilogue transposition buffer
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
   const int tid = threadIdx.x;
@@ -631,41 +652,46 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   const int lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
   const int lrow = lane & 31, lk = lane >> 5;
-  const int C = T.C, H = T.H, W = T.W, R = T.R, S = T.S, Q = T.Q, Kg = T.Kg;
+  const int C = T.C, H = T.H, W = T.W, R = T.R, S = T.S, P = T.P, Q = T.Q, Kg = T.Kg;
   const int SC = S * C;
-  const int qt = (Q + MT - 1) / MT;
-  const int np = (int)it.tile_m / qt;
-  const int q0 = ((int)it.tile_m - np * qt) * MT;
-  const int n = np / T.P, p = np - n * T.P;
+  const int qt = (Q + MT - 1) / MT;                 // pixel segments per output row
+  const int pg = (P + RT - 1) / RT;                 // row groups per image
+  const int npg = (int)it.tile_m / qt;
+  const int q0 = ((int)it.tile_m - npg * qt) * MT;
+  const int n = npg / pg;
+  const int p0 = (npg - n * pg) * RT;
+  const int nrows_out = (P - p0 < RT) ? (P - p0) : RT;
   const int n0 = (int)it.tile_n * NT;
   const __amdgpu_buffer_rsrc_t rx = make_rsrc(T.x, T.x_bytes);
   const __amdgpu_buffer_rsrc_t rw = make_rsrc(T.w, T.w_bytes);
 
-  // LDS: R image rows, each [pad*C zeros][W*C elements][zeros] starting on a 16-byte boundary, so that
-  // every pixel's patch (which starts stride*C elements after its neighbour's) is 4-byte aligned; then
-  // the filters.
+  // LDS: [transposition buffer][NR image rows][filters].  Each image row is [pad*C zeros][W*C elements]
+  // [zeros] starting on a 16-byte boundary, so that every pixel's patch (which starts stride*C elements
+  // after its neighbour's) is 4-byte aligned.
+  const int NR = R + T.stride * (RT - 1);                   // input rows held
   const int lpad = T.pad * C * 2;                           // bytes of left padding
   const int rowb = W * C * 2;                               // bytes of one image row (multiple of 16)
   const int pitch = ((lpad + rowb + lpad + 15) & ~15) + 64;
-  char* sW = smem + R * pitch;                              // [NT][R][KR] elements
+  char* sX = smem + kStageBytes;
+  char* sW = sX + NR * pitch;                               // [NT][R][KR] elements
+  const int h_first = p0 * T.stride - T.pad;
 
-  // 1. put the global loads in flight: all image rows (rows outside the image read as zeros) and the first
-  //    round of filter vectors (the tile's filters are one contiguous run of nf*Kg elements)
-  const int nvr = rowb / 16, total_rows = R * nvr;
+  // 1. put the global loads in flight: the first round of image-row vectors (rows outside the image read
+  //    as zeros) and of filter vectors (the tile's filters are one contiguous run of nf*Kg elements)
+  const int nvr = rowb / 16, total_rows = NR * nvr;
   const int nf = (T.K - n0 < NT) ? (T.K - n0) : NT;
   const int total_e = nf * Kg;
   const uint32_t wbase = (uint32_t)n0 * (uint32_t)Kg * 2u;
-  constexpr int RV = 4, RW = 5;                             // vectors per thread per round: image rows, filters
+  constexpr int RV = 5, RW = 5;                             // vectors per thread per round: image rows, filters
   u32x4 drow[RV], dw[RW];
-#pragma unroll
-  for (int u = 0; u < RV; ++u) {
-    const int v = u * kThreads + tid;
+  auto row_offset = [&](int v) -> uint32_t {
     const int r = v / nvr, i = v - r * nvr;
-    const int h = p * T.stride - T.pad + r;
+    const int h = h_first + r;
     const bool ok = (v < total_rows) & ((unsigned)h < (unsigned)H);
-    const uint32_t off = ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
-    drow[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
-  }
+    return ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
+  };
+#pragma unroll
+  for (int u = 0; u < RV; ++u) drow[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)row_offset(u * kThreads + tid), 0, 0);
 #pragma unroll
   for (int u = 0; u < RW; ++u)
     dw[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(wbase + (uint32_t)(u * kThreads + tid) * 16u), 0, 0);
@@ -673,10 +699,10 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   // 2. zero the padding of the rows and the whole filter array
   {
     const int zl = lpad / 2, zr = (pitch - lpad - rowb) / 2;   // elements left / right of the data
-    for (int r = wave; r < R; r += 4)
+    for (int r = wave; r < NR; r += 4)
       for (int e = lane; e < zl + zr; e += 64) {
         const int off = (e < zl) ? 2 * e : lpad + rowb + 2 * (e - zl);
-        *(uint16_t*)(smem + r * pitch + off) = 0;
+        *(uint16_t*)(sX + r * pitch + off) = 0;
       }
     for (int z = tid; z < NT * R * KR * 2 / 16; z += kThreads) *(u32x4*)(sW + z * 16) = u32x4{0u, 0u, 0u, 0u};
   }
@@ -684,7 +710,7 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   auto put_row_vector = [&](int v, const u32x4& d) {
     if (v < total_rows) {
       const int r = v / nvr, i = v - r * nvr;
-      char* dst = smem + r * pitch + lpad + i * 16;
+      char* dst = sX + r * pitch + lpad + i * 16;
       if ((lpad & 3) == 0) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) *(uint32_t*)(dst + 4 * e) = d[e];
@@ -698,14 +724,8 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   };
 #pragma unroll
   for (int u = 0; u < RV; ++u) put_row_vector(u * kThreads + tid, drow[u]);
-  for (int v0 = RV * kThreads; v0 < total_rows; v0 += kThreads) {      // rows longer than one round (rare)
-    const int v = v0 + tid;
-    const int r = v / nvr, i = v - r * nvr;
-    const int h = p * T.stride - T.pad + r;
-    const bool ok = (v < total_rows) & ((unsigned)h < (unsigned)H);
-    const uint32_t off = ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
-    put_row_vector(v, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0));
-  }
+  for (int v0 = RV * kThreads; v0 < total_rows; v0 += kThreads)       // wider images: further rounds
+    put_row_vector(v0 + tid, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)row_offset(v0 + tid), 0, 0));
   __syncthreads();   // the filter array is zeroed before the scatter below
   // 4. filters: scatter each element of the contiguous run to [filter][r][s*C+c]
   auto put_filter_vector = [&](int v, const u32x4& d) {
@@ -734,12 +754,6 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   __syncthreads();
   if (prof && tid == 0) prof[1] = __builtin_readcyclecounter();
 
-  Acc acc[BM][BN];
-#pragma unroll
-  for (int i = 0; i < BM; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
-
   // per-lane masks that clear the elements at or past S*C (they belong to the next pixel)
   uint32_t msk[2][4];
 #pragma unroll
@@ -758,28 +772,33 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
     qa[i] = q * T.stride * C * 2 + lk * 16;
   }
   const char* wrow = sW + (wn0 + lrow) * R * (KR * 2) + lk * 16;
-  for (int r = 0; r < R; ++r) {
-    const char* xr = smem + r * pitch;
+  const int q_end = (q0 + MT < Q) ? q0 + MT : Q;
+  for (int rt = 0; rt < nrows_out; ++rt) {
+    Acc acc[BM][BN];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      if (half < nh) {
-        const u32x4 wf = *(const u32x4*)(wrow + r * (KR * 2) + half * 32);
+    for (int i = 0; i < BM; ++i)
 #pragma unroll
-        for (int i = 0; i < BM; ++i) {
-          const uint32_t* src = (const uint32_t*)(xr + qa[i] + half * 32);
-          const u32x4 xf = {src[0] & msk[half][0], src[1] & msk[half][1], src[2] & msk[half][2], src[3] & msk[half][3]};
-          acc[i][0] = MMA::run(wf, xf, acc[i][0]);
+      for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
+    for (int r = 0; r < R; ++r) {
+      const char* xr = sX + (rt * T.stride + r) * pitch;
+      static_for<2>([&](auto HALF) {
+        constexpr int half = decltype(HALF)::value;
+        if (half < nh) {
+          const u32x4 wf = *(const u32x4*)(wrow + r * (KR * 2) + half * 32);
+          static_for<BM>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            const uint32_t* src = (const uint32_t*)(xr + qa[i] + half * 32);
+            const u32x4 xf = {src[0] & msk[half][0], src[1] & msk[half][1], src[2] & msk[half][2], src[3] & msk[half][3]};
+            acc[i][0] = MMA::run(wf, xf, acc[i][0]);
+          });
         }
-      }
+      });
     }
+    const int mrow = (n * P + p0 + rt) * Q;
+    tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
   }
-  if (prof && tid == 0) prof[2] = __builtin_readcyclecounter();
-
-  const int m0 = np * Q + q0;
-  const int m_end = np * Q + ((q0 + MT < Q) ? q0 + MT : Q);
-  tile_epilogue<MT, NT, BM, BN, MF>(T, acc, m0, m_end, n0, wm0, wn0, lrow, lk, tid, smem);
   if (prof && tid == 0) {
-    prof[3] = __builtin_readcyclecounter();
+    prof[2] = prof[3] = __builtin_readcyclecounter();
     prof[6] = wall_clock64();
   }
 }

@@ -109,14 +109,15 @@ static const double kFirstCost = 3000.0;
 static const double kStepCost[kNumTileCfgs] = {1770.0, 1240.0, 1180.0, 750.0, 1180.0, 890.0, 520.0};
 static const double kEpiCost[kNumTileCfgs] = {5200.0, 3000.0, 3100.0, 2000.0, 1200.0, 1100.0, 2800.0};
 static const double kRowStageCost = 6500.0;     // row tile: copying image rows and filters into LDS
-static const double kGenericStepFactor = 4.5;   // element-wise gathers are bound by the texture addresser
+static const double kGenericStepFactor = 2.8;   // element-wise gathers are bound by the texture addresser
+static const double kGenericFirstCost = 19000.0;
 static const double kSplitCost = 5000.0, kSplitPerElem = 1.0, kSplitRoundCost = 2700.0;   // hand-off grows with the tile
 static const int kSlots = 400;                  // two workgroups resident per compute unit (512), derated because
                                                 // co-resident workgroups share one LDS pipe
 static const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
 
 struct Option {
-  int cfg, split, steps_per_split;
+  int cfg, split, steps_per_split, rows_per_tile;
   int64_t items;
   double item_time, area;
 };
@@ -134,23 +135,27 @@ static bool row_tile_ok(const st_conv_desc& d) {
   const int Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
   const int reach = (Q - 1) * d.stride * d.C * 2 + 64;             // furthest byte a pixel operand read touches
   if (reach > pitch) return false;
-  return (int64_t)d.R * pitch + (int64_t)kTileShapes[kRowCfg].NT * d.R * 64 <= kSmemBytes;
+  const int64_t stage = (kTileShapes[kRowCfg].MT / 2) * (kTileShapes[kRowCfg].NT + 4) * 4;   // epilogue buffer
+  const int64_t rows = d.R + d.stride * (kRowsPerTile - 1);
+  return stage + rows * pitch + (int64_t)kTileShapes[kRowCfg].NT * d.R * 64 <= kSmemBytes;
 }
 
-static Option make_row_option(const st_conv_desc& d) {
+static Option make_row_option(const st_conv_desc& d, int rows_per_tile) {
   Option o;
+  o.rows_per_tile = rows_per_tile;
   const int P = (d.H + 2 * d.pad - d.R) / d.stride + 1, Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
   o.cfg = kRowCfg;
   o.split = 1;
   o.steps_per_split = d.R;
-  o.items = (int64_t)d.N * P * cdiv(Q, kTileShapes[kRowCfg].MT) * cdiv(d.K, kTileShapes[kRowCfg].NT);
-  o.item_time = kFirstCost + kRowStageCost + d.R * kStepCost[kRowCfg] + kEpiCost[kRowCfg];
+  o.items = (int64_t)d.N * cdiv(P, rows_per_tile) * cdiv(Q, kTileShapes[kRowCfg].MT) * cdiv(d.K, kTileShapes[kRowCfg].NT);
+  o.item_time = kFirstCost + kRowStageCost + 500.0 * rows_per_tile + rows_per_tile * (d.R * kStepCost[kRowCfg] + kEpiCost[kRowCfg]);
   o.area = o.item_time * (double)o.items;
   return o;
 }
 
 static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, int cfg, int split) {
   Option o;
+  o.rows_per_tile = 0;
   const int k_steps = cdiv(kbytes, kTileShapes[cfg].KB);
   split = std::max(1, std::min(split, std::min(k_steps, 65535)));
   const int per = cdiv(k_steps, split);
@@ -160,7 +165,7 @@ static Option make_option(int64_t M, int64_t Ng, int64_t kbytes, bool vec_ok, in
   o.steps_per_split = per;
   o.items = (int64_t)cdiv(M, kTileShapes[cfg].MT) * cdiv(Ng, kTileShapes[cfg].NT) * split;
   const double step = kStepCost[cfg] * (vec_ok ? 1.0 : kGenericStepFactor);
-  o.item_time = kFirstCost + per * step + kEpiCost[cfg] +
+  o.item_time = (vec_ok ? kFirstCost : kGenericFirstCost) + per * step + kEpiCost[cfg] +
                 (split > 1 ? kSplitCost + kSplitPerElem * kTileShapes[cfg].MT * kTileShapes[cfg].NT +
                                  kSplitRoundCost * ((split - 1) / 8) : 0.0);
   o.area = o.item_time * (double)o.items;
@@ -172,7 +177,7 @@ static std::vector<Option> tenant_options(const st_conv_desc& d, int64_t M, int6
   std::vector<Option> out;
   const bool row_ok = row_tile_ok(d);
   if (row_ok && (o.tile_cfg == 0 || o.tile_cfg - 1 == kRowCfg) && o.split_k <= 1) {
-    out.push_back(make_row_option(d));
+    for (int rt = 1; rt <= kRowsPerTile; rt *= 2) out.push_back(make_row_option(d, rt));
     if (o.tile_cfg - 1 == kRowCfg) return out;
   }
   for (int c = 0; c < kNumTileCfgs; ++c) {
@@ -352,7 +357,8 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       ti.row_tiled = (op.cfg == kRowCfg) ? 1 : 0;
       if (ti.row_tiled) {
         ti.k_steps = descs[t].R;
-        ti.tiles_m = descs[t].N * ti.P * cdiv(ti.Q, ti.MT);
+        ti.tiles_m = descs[t].N * cdiv(ti.P, op.rows_per_tile) * cdiv(ti.Q, ti.MT);
+        ti.rows_per_tile = op.rows_per_tile;
       }
       ti.tiles_n = cdiv(ti.Ngemm, ti.NT);
       ti.split_k = op.split;
@@ -414,6 +420,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.x_bytes = (uint32_t)((int64_t)d.N * d.C * d.H * d.W * elem_size(d.in_dtype));
       T.w_bytes = (uint32_t)(ti.Ngemm * ti.Kgemm * elem_size(d.in_dtype));
       T.y_bytes = (uint32_t)(ti.M * ti.Ngemm * elem_size(d.out_dtype));
+      T.rows_per_tile = ti.rows_per_tile;
     }
   } catch (const std::bad_alloc&) {
     delete p;

@@ -67,7 +67,8 @@ def _expected_tenant_major(plan, n_tenants):
         mt, nt, kb = sc.st_tile_shape(ti.tile_cfg)
         assert (mt, nt) == (ti.MT, ti.NT)
         if ti.row_tiled:       # pixel tiles are segments of single output rows
-            assert ti.tiles_m == (ti.M // (ti.P * ti.Q)) * ti.P * -(-ti.Q // mt) and ti.split_k == 1
+            assert ti.rows_per_tile >= 1 and ti.split_k == 1
+            assert ti.tiles_m == (ti.M // (ti.P * ti.Q)) * -(-ti.P // ti.rows_per_tile) * -(-ti.Q // mt)
         else:
             assert ti.tiles_m == -(-ti.M // mt)
         assert ti.tiles_n == -(-ti.Ngemm // nt)
@@ -139,7 +140,7 @@ def test_row_tile_is_chosen_for_the_stem_only_when_eligible():
     stem = synth.ConvShape(1, 3, 224, 224, 64, 7, 7, 2, 3)
     p = _host_plan([stem, synth.ConvShape(1, 3, 30, 26, 64, 7, 7, 2, 3), synth.ConvShape(1, 64, 56, 56, 64, 3, 3, 1, 1)])
     a, b, c = (sc.st_conv_plan_tenant_info(p, t) for t in range(3))
-    assert a.row_tiled == 1 and (a.MT, a.NT) == (128, 64) and a.tiles_m == 112 and a.k_steps == 7
+    assert a.row_tiled == 1 and (a.MT, a.NT) == (128, 64) and a.tiles_m == 112 // a.rows_per_tile and a.k_steps == 7
     assert b.row_tiled == 0      # image rows are not a multiple of 16 bytes: element-wise gather kernel
     assert c.row_tiled == 0
 
