@@ -143,6 +143,15 @@ st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream);
  * hip_streams[0] afterwards (e.g. a timing event) follows all tenants. */
 st_status st_conv_run_space_only(const st_plan* plan, void* const* hip_streams, int32_t n_streams);
 
+/* The two baselines with one plan per tenant: every plan is issued as its own launch, serially on one
+ * stream (time-only) or plan i on hip_streams[i % n_streams] with the same fork/join convention as
+ * st_conv_run_space_only.  Planning each tenant alone lets its tiles and split-K factor suit a launch
+ * that has the whole GPU to itself, which is the fairest form of the paper's baselines (Section 4.1
+ * used a separately tuned single-problem kernel for them).  Empty (zero-tenant) plans are skipped. */
+st_status st_conv_run_plans_time_only(const st_plan* const* plans, int32_t n_plans, void* hip_stream);
+st_status st_conv_run_plans_space_only(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
+                                       int32_t n_streams);
+
 /* Replace tenant pointers (the cached-plan path of Section 4: same shapes, new inputs).  NULL keeps
  * the current pointer.  Synchronous small upload on the default stream; not for use while a run of
  * this plan is in flight. */

@@ -501,6 +501,52 @@ extern "C" st_status st_conv_run_space_only(const st_plan* plan, void* const* hi
   return ST_OK;
 }
 
+// Baselines with per-tenant plans: each plan (normally one tenant, planned alone so that its tiles suit a
+// launch that has the whole GPU to itself) is issued as its own fused launch.
+extern "C" st_status st_conv_run_plans_time_only(const st_plan* const* plans, int32_t n_plans, void* hip_stream) {
+  if (n_plans < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or n_plans negative");
+  for (int32_t i = 0; i < n_plans; ++i) {
+    st_status s = st_conv_run(plans[i], hip_stream);
+    if (s != ST_OK) return s;
+  }
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run_plans_space_only(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
+                                                  int32_t n_streams) {
+  if (n_plans < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or n_plans negative");
+  if (!hip_streams || n_streams <= 0) return fail(ST_ERR_INVALID_ARG, "need at least one stream");
+  if (n_plans == 0) return ST_OK;
+  for (int32_t i = 0; i < n_plans; ++i) {
+    st_status s = check_runnable(plans[i]);
+    if (s != ST_OK) return s;
+  }
+  hipStream_t anchor = (hipStream_t)hip_streams[0];
+  const int32_t used = std::min(n_plans, n_streams);
+  // fork: plans[0]'s event marks the work already queued on the anchor stream
+  const st_plan* first = nullptr;
+  for (int32_t i = 0; i < n_plans && !first; ++i)
+    if (plans[i]->ev_fork) first = plans[i];
+  if (used > 1 && first) {
+    ST_HIP(hipEventRecord(first->ev_fork, anchor));
+    for (int32_t i = 1; i < used; ++i) ST_HIP(hipStreamWaitEvent((hipStream_t)hip_streams[i], first->ev_fork, 0));
+  }
+  for (int32_t i = 0; i < n_plans; ++i) {
+    st_status s = st_conv_run(plans[i], hip_streams[i % n_streams]);
+    if (s != ST_OK) return s;
+  }
+  // join: the last plan issued on each non-anchor stream lends its event
+  for (int32_t sidx = 1; sidx < used; ++sidx) {
+    const st_plan* last = nullptr;
+    for (int32_t i = sidx; i < n_plans; i += n_streams)
+      if (!plans[i]->ev_join.empty()) last = plans[i];
+    if (!last) continue;
+    ST_HIP(hipEventRecord(last->ev_join[0], (hipStream_t)hip_streams[sidx]));
+    ST_HIP(hipStreamWaitEvent(anchor, last->ev_join[0], 0));
+  }
+  return ST_OK;
+}
+
 extern "C" st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const void* x, const void* w, void* y,
                                          const void* residual) {
   if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");

@@ -19,7 +19,7 @@ ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
-           "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
+           "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.st_conv_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
         L.st_conv_plan_rebind.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.st_conv_run_plans_time_only.argtypes = [P(vp), i32, vp]
+        L.st_conv_run_plans_space_only.argtypes = [P(vp), i32, P(vp), i32]
         L.st_conv_plan_info.argtypes = [vp, P(st_plan_info)]
         L.st_conv_plan_tenant_info.argtypes = [vp, i32, P(st_tenant_info)]
         L.st_conv_plan_worklist.argtypes = [vp, i32, P(P(st_work_item)), P(i64)]
@@ -101,7 +103,8 @@ def lib() -> ctypes.CDLL:
         L.st_status_string.restype = ctypes.c_char_p
         L.st_last_error_message.argtypes = []
         L.st_last_error_message.restype = ctypes.c_char_p
-        for name in ("st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
+        for name in ("st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_plans_time_only",
+                     "st_conv_run_plans_space_only", "st_conv_run_time_only", "st_conv_run_space_only",
                      "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info",
                      "st_conv_plan_worklist", "st_tile_shape", "st_tile_count",
                      "st_maxpool_nhwc", "st_launch_empty", "st_launch_copy"):
@@ -199,6 +202,20 @@ def st_conv_run_space_only(plan: Plan, streams) -> None:
     hs = [_stream(s) for s in streams]
     arr = (ctypes.c_void_p * max(len(hs), 1))(*hs)
     _check(lib().st_conv_run_space_only(plan.handle, arr, len(hs)), "st_conv_run_space_only")
+
+
+def _plan_array(plans):
+    return (ctypes.c_void_p * max(len(plans), 1))(*[p.handle for p in plans])
+
+
+def st_conv_run_plans_time_only(plans, stream=None) -> None:
+    _check(lib().st_conv_run_plans_time_only(_plan_array(plans), len(plans), _stream(stream)), "st_conv_run_plans_time_only")
+
+
+def st_conv_run_plans_space_only(plans, streams) -> None:
+    hs = [_stream(s) for s in streams]
+    arr = (ctypes.c_void_p * max(len(hs), 1))(*hs)
+    _check(lib().st_conv_run_plans_space_only(_plan_array(plans), len(plans), arr, len(hs)), "st_conv_run_plans_space_only")
 
 
 def st_conv_plan_rebind(plan: Plan, tenant: int, x=None, w=None, y=None, residual=None) -> None:

@@ -124,6 +124,48 @@ def test_split_k_is_deterministic(torch):
         helpers.check_tenant(t, f"split-K tenant {i}")
 
 
+def test_per_tenant_plan_baselines(torch):
+    """Baselines with one plan per tenant (each planned alone) match the oracle too."""
+    from tests import helpers
+    tenants = helpers.make_tenants(2)
+    plans = [helpers.plan_for([t]) for t in tenants]
+    sc.st_conv_run_plans_time_only(plans)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"time-only, own plan, tenant {i}")
+        t.clear()
+    streams = [torch.cuda.Stream() for _ in tenants]
+    sc.st_conv_run_plans_space_only(plans, streams[:3])        # fewer streams than plans
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"space-only, own plan, tenant {i}")
+    sc.st_conv_run_plans_time_only([])
+    sc.st_conv_run_plans_space_only([], streams)
+
+
+def test_split_k_workspace_is_not_stale_across_inputs(torch):
+    """The split-K workspace is reused by every run of a plan.  Feeding different inputs through the same
+    plan (rebind) must give the new inputs' result: a read of a stale cached partial would reproduce the
+    previous run's values instead."""
+    from tests import helpers
+    shape = synth.config_shapes(2)[3]            # 49 x 512 x 4608: split-K territory
+    a = helpers.Tenant(shape, synth.gen_input(93, 0, 0, shape), synth.gen_weight(93, 0, 0, shape))
+    b = helpers.Tenant(shape, synth.gen_input(93, 1, 0, shape), synth.gen_weight(93, 1, 0, shape))
+    plan = helpers.plan_for([a], tile_cfg=4, split_k=9)
+    assert sc.st_conv_plan_tenant_info(plan, 0).split_k == 9
+    for rep in range(3):
+        sc.st_conv_plan_rebind(plan, 0, x=a.dx, w=a.dw, y=a.dy)
+        sc.st_conv_run(plan)
+        _sync(torch)
+        helpers.check_tenant(a, f"rep {rep} inputs A")
+        sc.st_conv_plan_rebind(plan, 0, x=b.dx, w=b.dw, y=b.dy)
+        sc.st_conv_run(plan)
+        _sync(torch)
+        helpers.check_tenant(b, f"rep {rep} inputs B")
+        assert not torch.equal(a.dy, b.dy)
+        a.clear(); b.clear()
+
+
 @pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 def test_epilogue_residual_relu(torch, out_dtype):
     from tests import helpers
