@@ -168,6 +168,30 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
     float* sC = (float*)smem;
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(has_res ? T.res : T.y, T.y_bytes);
+    // Residual vectors are requested before the accumulators are staged, so their latency overlaps the
+    // transposition (single-slice tiles only).
+    constexpr int IT32 = (MP * (NT / 4) + kThreads - 1) / kThreads, IT16 = (MP * (NT / 8) + kThreads - 1) / kThreads;
+    constexpr bool kPrefetchRes = (PASSES == 1);
+    u32x4 rpre[kPrefetchRes ? IT32 : 1];
+    if (kPrefetchRes && has_res) {
+      if (T.out_dtype == ST_DT_F32) {
+#pragma unroll
+        for (int u = 0; u < IT32; ++u) {
+          const int v = u * kThreads + tid;
+          const int m = m0 + v / (NT / 4), ch = n0 + (v % (NT / 4)) * 4;
+          const bool ok = (MP * (NT / 4) % kThreads == 0 || v < MP * (NT / 4)) & (m < m_end) & (ch < Kf);
+          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset), 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < IT16; ++u) {
+          const int v = u * kThreads + tid;
+          const int m = m0 + v / (NT / 8), ch = n0 + (v % (NT / 8)) * 8;
+          const bool ok = (MP * (NT / 8) % kThreads == 0 || v < MP * (NT / 8)) & (m < m_end) & (ch < Kf);
+          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset), 0, 0);
+        }
+      }
+    }
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
     const int mp0 = m0 + pass * MP;   // first im2col row of this slice
@@ -206,7 +230,8 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
         }
         if (has_res) {
 #pragma unroll
-          for (int u = 0; u < UB; ++u) a[u] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
+          for (int u = 0; u < UB; ++u)
+            a[u] += __builtin_bit_cast(f32x4, kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
         }
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
@@ -240,7 +265,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
         if (has_res) {
 #pragma unroll
           for (int u = 0; u < UB; ++u) {
-            const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
+            const u32x4 r = kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const uint16_t h0 = (uint16_t)(r[e >> 1] >> (16 * (e & 1))), h1 = (uint16_t)(r[2 + (e >> 1)] >> (16 * (e & 1)));
