@@ -71,8 +71,10 @@ typedef struct st_plan_opts {
   int32_t split_k;       /* 0 = choose per tenant; >= 1 forces that factor (clamped to the K steps)  */
   int32_t order;         /* 0 = longest work item first (default); 1 = tenant-major                  */
   int32_t host_only;     /* 1 = build the tables on the host only (no device calls); run => error    */
-  int32_t target_items;  /* 0 = default (512); else workgroup slots the planner's cost model fills     */
-  int32_t reserved[3];   /* must be 0                                                                */
+  int32_t target_items;  /* 0 = default; else the workgroup slots the planner's cost model fills      */
+  int32_t rows_per_tile; /* 0 = choose; 1, 2 or 4 forces the output rows per work item of row-tiled   */
+                         /* tenants (ignored for the others)                                         */
+  int32_t reserved[2];   /* must be 0                                                                */
 } st_plan_opts;
 
 /* One workgroup's assignment: the bit-exact object of the plan.  tile_m counts pixel tiles (MT rows

@@ -53,11 +53,12 @@ struct TenantDev {
   int32_t tap_uniform;   // 1: C is a multiple of the K step, so each step lies within one filter tap
   int32_t shift_c, shift_s;   // floor(n/d) = ((n * magic) >> 31) >> shift, for d = C and d = S
   uint32_t magic_c, magic_s;
-  int32_t shift_sc, shift_kg;   // same for d = S*C and d = Kgemm (row tile only)
-  uint32_t magic_sc, magic_kg;
+  int32_t shift_r, shift_nvp; // same for d = R and d = row_pitch/16 (row tile only)
+  uint32_t magic_r, magic_nvp;
   uint32_t x_bytes, w_bytes;  // buffer sizes for bounds-checked loads
   uint32_t y_bytes;           // size of y (and of the residual) in bytes
   int32_t rows_per_tile;      // row tile only: output rows per work item
+  int32_t row_pitch;          // row tile only: bytes of one image row in LDS (padding included, multiple of 16)
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 

@@ -651,15 +651,30 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   }
 }
 
+// The 128 bits that start kk 16-bit elements into the 256-bit value hi:lo (kk wave-uniform, 0..8).
+__device__ __forceinline__ u32x4 window128(const u32x4& lo, const u32x4& hi, int kk) {
+  const uint32_t b = (uint32_t)(kk & 1) * 16u;
+  uint32_t w0, w1, w2, w3, w4;
+  switch (kk >> 1) {
+    case 0: w0 = lo[0]; w1 = lo[1]; w2 = lo[2]; w3 = lo[3]; w4 = hi[0]; break;
+    case 1: w0 = lo[1]; w1 = lo[2]; w2 = lo[3]; w3 = hi[0]; w4 = hi[1]; break;
+    case 2: w0 = lo[2]; w1 = lo[3]; w2 = hi[0]; w3 = hi[1]; w4 = hi[2]; break;
+    case 3: w0 = lo[3]; w1 = hi[0]; w2 = hi[1]; w3 = hi[2]; w4 = hi[3]; break;
+    default: w0 = hi[0]; w1 = hi[1]; w2 = hi[2]; w3 = hi[3]; w4 = 0u; break;
+  }
+  return u32x4{__builtin_amdgcn_alignbit(w1, w0, b), __builtin_amdgcn_alignbit(w2, w1, b),
+               __builtin_amdgcn_alignbit(w3, w2, b), __builtin_amdgcn_alignbit(w4, w3, b)};
+}
+
 // ---- row tile for layers with very few input channels ---------------------------------------------
 // For the 7x7 / stride-2 / 3-channel stem the im2col row of one (pixel, filter row r) is S*C = 21
 // contiguous elements of the NHWC image, at an odd element offset, so neither 16-byte gathers nor the
 // element-wise gather variant are efficient.  This kernel gives one workgroup kRowsPerTile consecutive
 // output rows (a segment of up to 128 pixels of each) x 64 filters: the input rows they need are copied
-// whole into LDS with aligned 16-byte loads (rows outside the image and the left/right padding are
-// zeros), the 64 filters are copied once into an LDS array [filter][r][32] padded with zeros, and the
-// MFMA operands are assembled from LDS.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by
-// the planner: 16-bit types, S*C <= 32, W*C*2 a multiple of 16, stride*C even, LDS footprint.
+// whole into LDS with 16-byte loads (rows outside the image and the left/right padding are zeros), the
+// 64 filters are copied once into an LDS array [filter][r][32] padded with zeros, and the MFMA operands
+// are assembled from LDS.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by the planner:
+// 16-bit types, 8 <= S*C <= 32, W*C*2 a multiple of 16, stride*C even, LDS footprint.
 template <int DT>
 __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
@@ -696,85 +711,89 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   const int NR = R + T.stride * (RT - 1);                   // input rows held
   const int lpad = T.pad * C * 2;                           // bytes of left padding
   const int rowb = W * C * 2;                               // bytes of one image row (multiple of 16)
-  const int pitch = ((lpad + rowb + lpad + 15) & ~15) + 64;
+  const int pitch = T.row_pitch;                            // bytes of one LDS row (multiple of 16)
   char* sX = smem + kStageBytes;
   char* sW = sX + NR * pitch;                               // [NT][R][KR] elements
   const int h_first = p0 * T.stride - T.pad;
 
-  // 1. put the global loads in flight: the first round of image-row vectors (rows outside the image read
-  //    as zeros) and of filter vectors (the tile's filters are one contiguous run of nf*Kg elements)
-  const int nvr = rowb / 16, total_rows = NR * nvr;
+  // Both arrays are written as whole 16-byte vectors in linear order, each from one 16-byte load at a
+  // 2-byte-aligned address; a round of 256 filter vectors covers 64 (filter, filter row) pairs with the
+  // position inside the filter row fixed per thread.  An image-row vector that straddles an end of the
+  // row data, and the last vector of a filter row, are loaded from the nearest position that lies wholly
+  // inside the row and shifted into place (zeros move in), so no load touches bytes outside its own row.
+  // All loads of the first round are put in flight before the first LDS write.
+  const int nvp = pitch >> 4, total_rv = NR * nvp;
+  const int sl = (lpad & 15) >> 1;                          // elements the row data sits past a vector boundary
+  const int jl = lpad >> 4, jr = (lpad + rowb) >> 4;        // the two straddling vectors of a row (when sl != 0)
   const int nf = (T.K - n0 < NT) ? (T.K - n0) : NT;
-  const int total_e = nf * Kg;
-  const uint32_t wbase = (uint32_t)n0 * (uint32_t)Kg * 2u;
-  constexpr int RV = 5, RW = 5;                             // vectors per thread per round: image rows, filters
-  u32x4 drow[RV], dw[RW];
-  auto row_offset = [&](int v) -> uint32_t {
-    const int r = v / nvr, i = v - r * nvr;
-    const int h = h_first + r;
-    const bool ok = (v < total_rows) & ((unsigned)h < (unsigned)H);
-    return ok ? (uint32_t)((n * H + h) * W) * (uint32_t)(C * 2) + (uint32_t)i * 16u : kInvalidOffset;
+  const int nvec = (SC + 7) >> 3;                           // vectors of a filter row that hold data
+  const int kkw = 8 * nvec - SC;                            // elements the last of them is loaded early by
+  const int npairs = NT * R;                                // (filter, filter row) pairs
+  constexpr int RB = 5, RW = 7;                             // rounds per batch: image-row vectors, filter vectors
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  auto row_base = [&](int r) -> uint32_t { return (uint32_t)((n * H + h_first + r) * W) * (uint32_t)(C * 2); };
+  auto row_load = [&](int v, bool& mine) -> u32x4 {
+    const int r = fast_div(v, T.magic_nvp, T.shift_nvp), j = v - r * nvp;
+    const int sj = 16 * j - lpad;                           // byte position of this vector in the row data
+    const bool ok = (v < total_rv) & ((unsigned)(h_first + r) < (unsigned)H) & (sj >= 0) & (sj + 16 <= rowb);
+    mine = (v < total_rv) & !((sl != 0) & ((j == jl) | (j == jr)));      // the straddlers are written below
+    return __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(r) + (uint32_t)sj : kInvalidOffset), 0, 0);
   };
+  auto row_store = [&](int v, const u32x4& d, bool mine) {
+    if (mine) *(u32x4*)(sX + v * 16) = d;
+  };
+  const int slot = tid & 3;                                 // 16-byte position inside a padded filter row
+  const bool lastslot = slot == nvec - 1;
+  const int e0 = lastslot ? SC - 8 : slot * 8;
+  const uint32_t mlast = lastslot ? 0xffffffffu : 0u;
+  auto w_load = [&](int cr) -> u32x4 {
+    const int ch = fast_div(cr, T.magic_r, T.shift_r), r = cr - ch * R;
+    const bool live = (slot < nvec) & (cr < npairs) & (ch < nf);
+    const uint32_t off = live ? ((uint32_t)(n0 + ch) * (uint32_t)Kg + (uint32_t)(r * SC + e0)) * 2u : kInvalidOffset;
+    return __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
+  };
+  auto w_store = [&](int cr, u32x4 d) {
+    if (kkw != 0) {
+      const u32x4 ds = window128(d, zero4, kkw);
 #pragma unroll
-  for (int u = 0; u < RV; ++u) drow[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)row_offset(u * kThreads + tid), 0, 0);
+      for (int e = 0; e < 4; ++e) d[e] = (ds[e] & mlast) | (d[e] & ~mlast);
+    }
+    if (cr < npairs) *(u32x4*)(sW + (cr * 4 + slot) * 16) = d;
+  };
+  u32x4 drow[RB], dw[RW], dfix = zero4;
+  bool rmine[RB];
+  const int fr = tid >> 1, fside = tid & 1;                 // straddler (row, end) handled by this thread
 #pragma unroll
-  for (int u = 0; u < RW; ++u)
-    dw[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(wbase + (uint32_t)(u * kThreads + tid) * 16u), 0, 0);
-
-  // 2. zero the padding of the rows and the whole filter array
-  {
-    const int zl = lpad / 2, zr = (pitch - lpad - rowb) / 2;   // elements left / right of the data
-    for (int r = wave; r < NR; r += 4)
-      for (int e = lane; e < zl + zr; e += 64) {
-        const int off = (e < zl) ? 2 * e : lpad + rowb + 2 * (e - zl);
-        *(uint16_t*)(sX + r * pitch + off) = 0;
-      }
-    for (int z = tid; z < NT * R * KR * 2 / 16; z += kThreads) *(u32x4*)(sW + z * 16) = u32x4{0u, 0u, 0u, 0u};
+  for (int u = 0; u < RB; ++u) drow[u] = row_load(u * kThreads + tid, rmine[u]);
+  if (sl != 0) {
+    const bool ok = (fr < NR) & ((unsigned)(h_first + fr) < (unsigned)H);
+    dfix = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(fr) + (uint32_t)(fside ? rowb - 16 : 0) : kInvalidOffset), 0, 0);
   }
-  // 3. image rows into LDS; the data starts lpad bytes into the row, i.e. 4-byte aligned or 2 bytes off
-  auto put_row_vector = [&](int v, const u32x4& d) {
-    if (v < total_rows) {
-      const int r = v / nvr, i = v - r * nvr;
-      char* dst = sX + r * pitch + lpad + i * 16;
-      if ((lpad & 3) == 0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) *(uint32_t*)(dst + 4 * e) = d[e];
-      } else {
-        *(uint16_t*)dst = (uint16_t)d[0];
+  for (int u = 0; u < RW; ++u) dw[u] = w_load((tid >> 2) + 64 * u);
 #pragma unroll
-        for (int e = 0; e < 3; ++e) *(uint32_t*)(dst + 2 + 4 * e) = (d[e] >> 16) | (d[e + 1] << 16);
-        *(uint16_t*)(dst + 14) = (uint16_t)(d[3] >> 16);
-      }
-    }
-  };
+  for (int u = 0; u < RB; ++u) row_store(u * kThreads + tid, drow[u], rmine[u]);
+  for (int v0 = RB * kThreads; v0 < total_rv; v0 += kThreads) {       // wider images: further rounds
+    bool mine;
+    const u32x4 d = row_load(v0 + tid, mine);
+    row_store(v0 + tid, d, mine);
+  }
+  if (sl != 0) {
+    // left end: the data moves up by sl elements; right end: down by 8 - sl; both are the window that starts
+    // 8 - sl elements into (data, zeros) resp. (zeros, data)
+    const uint32_t ms = fside ? 0xffffffffu : 0u;
+    const u32x4 lo = {dfix[0] & ms, dfix[1] & ms, dfix[2] & ms, dfix[3] & ms};
+    const u32x4 hi = {dfix[0] & ~ms, dfix[1] & ~ms, dfix[2] & ~ms, dfix[3] & ~ms};
+    const u32x4 d = window128(lo, hi, 8 - sl);
+    if (fr < NR) *(u32x4*)(sX + fr * pitch + (fside ? jr : jl) * 16) = d;
+  }
 #pragma unroll
-  for (int u = 0; u < RV; ++u) put_row_vector(u * kThreads + tid, drow[u]);
-  for (int v0 = RV * kThreads; v0 < total_rows; v0 += kThreads)       // wider images: further rounds
-    put_row_vector(v0 + tid, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)row_offset(v0 + tid), 0, 0));
-  __syncthreads();   // the filter array is zeroed before the scatter below
-  // 4. filters: scatter each element of the contiguous run to [filter][r][s*C+c]
-  auto put_filter_vector = [&](int v, const u32x4& d) {
-    int f = v * 8;
-    if (f < total_e) {
-      int ch = fast_div(f, T.magic_kg, T.shift_kg);
-      const int rem = f - ch * Kg;
-      int r = fast_div(rem, T.magic_sc, T.shift_sc);
-      int j = rem - r * SC;
+  for (int u = 0; u < RW; ++u) w_store((tid >> 2) + 64 * u, dw[u]);
+  for (int c0 = 64 * RW; c0 < npairs; c0 += 64 * RW) {     // taller filters
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (f + e < total_e) *(uint16_t*)(sW + ((ch * R + r) * KR + j) * 2) = (uint16_t)(d[e >> 1] >> (16 * (e & 1)));
-        if (++j == SC) { j = 0; if (++r == R) { r = 0; ++ch; } }
-      }
-    }
-  };
+    for (int u = 0; u < RW; ++u) dw[u] = w_load(c0 + (tid >> 2) + 64 * u);
 #pragma unroll
-  for (int u = 0; u < RW; ++u) put_filter_vector(u * kThreads + tid, dw[u]);
-  for (int v0 = RW * kThreads; v0 * 8 < total_e; v0 += RW * kThreads) {
-#pragma unroll
-    for (int u = 0; u < RW; ++u)
-      dw[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(wbase + (uint32_t)(v0 + u * kThreads + tid) * 16u), 0, 0);
-#pragma unroll
-    for (int u = 0; u < RW; ++u) put_filter_vector(v0 + u * kThreads + tid, dw[u]);
+    for (int u = 0; u < RW; ++u) w_store(c0 + (tid >> 2) + 64 * u, dw[u]);
   }
   __syncthreads();
   if (prof && tid == 0) prof[1] = __builtin_readcyclecounter();
@@ -798,27 +817,48 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   }
   const char* wrow = sW + (wn0 + lrow) * R * (KR * 2) + lk * 16;
   const int q_end = (q0 + MT < Q) ? q0 + MT : Q;
+  // operands of one (filter row, half): the filter vector and BM masked pixel vectors
+  struct Ops { u32x4 wf; u32x4 xf[BM]; };
+  auto fetch = [&](auto HALF, int rt, int r, Ops& o) {
+    constexpr int half = decltype(HALF)::value;
+    const char* xr = sX + (rt * T.stride + r) * pitch + half * 32;
+    o.wf = *(const u32x4*)(wrow + r * (KR * 2) + half * 32);
+#pragma unroll
+    for (int i = 0; i < BM; ++i) {
+      const uint32_t* src = (const uint32_t*)(xr + qa[i]);
+      o.xf[i] = u32x4{src[0], src[1], src[2], src[3]};
+    }
+  };
+  // masking is left to the point of use, so that the LDS reads stay in flight behind the other half's MFMAs
+  auto mma = [&](auto HALF, const Ops& o, Acc (&acc)[BM][BN]) {
+    constexpr int half = decltype(HALF)::value;
+#pragma unroll
+    for (int i = 0; i < BM; ++i) {
+      const u32x4 xf = {o.xf[i][0] & msk[half][0], o.xf[i][1] & msk[half][1], o.xf[i][2] & msk[half][2], o.xf[i][3] & msk[half][3]};
+      acc[i][0] = MMA::run(o.wf, xf, acc[i][0]);
+    }
+  };
   for (int rt = 0; rt < nrows_out; ++rt) {
     Acc acc[BM][BN];
 #pragma unroll
     for (int i = 0; i < BM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][0][v] = 0.f;
-    for (int r = 0; r < R; ++r) {
-      const char* xr = sX + (rt * T.stride + r) * pitch;
-      static_for<2>([&](auto HALF) {
-        constexpr int half = decltype(HALF)::value;
-        if (half < nh) {
-          const u32x4 wf = *(const u32x4*)(wrow + r * (KR * 2) + half * 32);
-          static_for<BM>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            const uint32_t* src = (const uint32_t*)(xr + qa[i] + half * 32);
-            const u32x4 xf = {src[0] & msk[half][0], src[1] & msk[half][1], src[2] & msk[half][2], src[3] & msk[half][3]};
-            acc[i][0] = MMA::run(wf, xf, acc[i][0]);
-          });
-        }
-      });
-    }
+    // the operands of the next half step are fetched from LDS while the MFMAs of the current one run; the
+    // loop exists once per number of halves so that its body is free of branches
+    auto k_loop = [&](auto NH) {
+      constexpr int halves = decltype(NH)::value;
+      Ops o0, o1;
+      fetch(std::integral_constant<int, 0>{}, rt, 0, o0);
+      for (int r = 0; r < R; ++r) {
+        if constexpr (halves > 1) fetch(std::integral_constant<int, 1>{}, rt, r, o1);
+        mma(std::integral_constant<int, 0>{}, o0, acc);
+        // the last iteration fetches filter row R - 1 again instead of branching around the reads
+        fetch(std::integral_constant<int, 0>{}, rt, (r + 1 < R) ? r + 1 : r, o0);
+        if constexpr (halves > 1) mma(std::integral_constant<int, 1>{}, o1, acc);
+      }
+    };
+    if (nh > 1) k_loop(std::integral_constant<int, 2>{}); else k_loop(std::integral_constant<int, 1>{});
     const int mrow = (n * P + p0 + rt) * Q;
     tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
   }

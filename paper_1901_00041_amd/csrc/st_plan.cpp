@@ -124,14 +124,22 @@ struct Option {
 
 // Row tile eligibility (see conv_tile_rows): 16-bit types, S*C <= 32, image rows a multiple of 16 bytes,
 // stride*C even, LDS footprint within the allocation.
+// Bytes of one image row in the row tile's LDS array: left padding, the row, right padding, rounded up to
+// whole 16-byte vectors, plus the 64 bytes the operand read of the last pixel may run past its patch.
+static int row_tile_pitch(const st_conv_desc& d) {
+  const int64_t lpad = (int64_t)d.pad * d.C * 2;
+  const int64_t pitch = ((lpad + (int64_t)d.W * d.C * 2 + lpad + 15) & ~(int64_t)15) + 64;
+  return (int)std::min<int64_t>(pitch, 1 << 24);
+}
+
 static bool row_tile_ok(const st_conv_desc& d) {
   if (d.in_dtype == ST_DT_F32) return false;
   if (d.C % 8 == 0) return false;                       // the vector kernels are better
-  if (d.S * d.C > 32) return false;
+  if (d.S * d.C > 32 || d.S * d.C < 8) return false;    // a filter row is one K step of 32, loaded as 16-byte vectors
   if ((d.W * d.C * 2) % 16 != 0) return false;
   if ((d.stride * d.C * 2) % 4 != 0) return false;       // pixel patches must stay 4-byte aligned in LDS
-  const int lpad = d.pad * d.C * 2;
-  const int pitch = ((lpad + d.W * d.C * 2 + lpad + 15) & ~15) + 64;
+  const int pitch = row_tile_pitch(d);
+  if (d.R + d.stride * (kRowsPerTile - 1) > kThreads / 2) return false;   // one thread per row end
   const int Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
   const int reach = (Q - 1) * d.stride * d.C * 2 + 64;             // furthest byte a pixel operand read touches
   if (reach > pitch) return false;
@@ -177,7 +185,8 @@ static std::vector<Option> tenant_options(const st_conv_desc& d, int64_t M, int6
   std::vector<Option> out;
   const bool row_ok = row_tile_ok(d);
   if (row_ok && (o.tile_cfg == 0 || o.tile_cfg - 1 == kRowCfg) && o.split_k <= 1) {
-    for (int rt = 1; rt <= kRowsPerTile; rt *= 2) out.push_back(make_row_option(d, rt));
+    for (int rt = 1; rt <= kRowsPerTile; rt *= 2)
+      if (o.rows_per_tile == 0 || o.rows_per_tile == rt) out.push_back(make_row_option(d, rt));
     if (o.tile_cfg - 1 == kRowCfg) return out;
   }
   for (int c = 0; c < kNumTileCfgs; ++c) {
@@ -307,7 +316,9 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
   if (o.tile_cfg < 0 || o.tile_cfg > kNumTileCfgs) return fail(ST_ERR_INVALID_ARG, "opts.tile_cfg out of range");
-  if (o.split_k < 0 || o.order < 0 || o.order > 1 || o.target_items < 0)
+  if (o.split_k < 0 || o.order < 0 || o.order > 1 || o.target_items < 0 ||
+      !(o.rows_per_tile == 0 || o.rows_per_tile == 1 || o.rows_per_tile == 2 || o.rows_per_tile == 4) ||
+      o.reserved[0] != 0 || o.reserved[1] != 0)
     return fail(ST_ERR_INVALID_ARG, "opts: negative or unknown value");
   for (int t = 0; t < n_tenants; ++t) {
     st_status s = validate(descs[t], t);
@@ -415,8 +426,9 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0) ? 1 : 0;
       magic_for(d.C, &T.magic_c, &T.shift_c);
       magic_for(d.S, &T.magic_s, &T.shift_s);
-      magic_for(d.S * d.C, &T.magic_sc, &T.shift_sc);
-      magic_for((int)std::min<int64_t>(ti.Kgemm, (1 << 20) - 1), &T.magic_kg, &T.shift_kg);
+      T.row_pitch = row_tile_pitch(d);
+      magic_for(T.row_pitch / 16, &T.magic_nvp, &T.shift_nvp);
+      magic_for(d.R, &T.magic_r, &T.shift_r);
       T.x_bytes = (uint32_t)((int64_t)d.N * d.C * d.H * d.W * elem_size(d.in_dtype));
       T.w_bytes = (uint32_t)(ti.Ngemm * ti.Kgemm * elem_size(d.in_dtype));
       T.y_bytes = (uint32_t)(ti.M * ti.Ngemm * elem_size(d.out_dtype));

@@ -33,8 +33,9 @@ class st_conv_desc(ctypes.Structure):
 
 
 class st_plan_opts(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("tile_cfg", "split_k", "order", "host_only", "target_items")] + \
-               [("reserved", ctypes.c_int32 * 3)]
+    _fields_ = [(n, ctypes.c_int32) for n in ("tile_cfg", "split_k", "order", "host_only", "target_items",
+                                                 "rows_per_tile")] + \
+               [("reserved", ctypes.c_int32 * 2)]
 
 
 class st_work_item(ctypes.Structure):
@@ -170,9 +171,10 @@ def st_conv_plan(descs: Sequence[st_conv_desc], opts: Optional[st_plan_opts] = N
     return Plan(out.value, keep)
 
 
-def plan_opts(tile_cfg=0, split_k=0, order=0, host_only=0, target_items=0) -> st_plan_opts:
+def plan_opts(tile_cfg=0, split_k=0, order=0, host_only=0, target_items=0, rows_per_tile=0) -> st_plan_opts:
     o = st_plan_opts()
     o.tile_cfg, o.split_k, o.order, o.host_only, o.target_items = tile_cfg, split_k, order, host_only, target_items
+    o.rows_per_tile = rows_per_tile
     return o
 
 

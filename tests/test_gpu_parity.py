@@ -56,6 +56,36 @@ def test_every_tile_shape_and_split(torch, tile_cfg, split_k):
     _run_small(torch, helpers, tile_cfg=tile_cfg, split_k=split_k)
 
 
+# Row tile (few input channels): every combination of how the row data sits against the 16-byte vectors of its
+# LDS copy (left padding of 0, 6, 8, 18, 24 bytes), of how a filter row of S*C elements ends inside its last
+# vector (S*C = 9, 10, 16, 21, 28, 30), ragged filter counts, filters taller than the 7 rows one round stages,
+# images wider than one round of row vectors, one and several pixel segments per output row.
+ROW_SHAPES = [
+    ConvShape(1, 4, 10, 24, 64, 2, 4, 1, 2, "bf16", "f32"),      # S*C = 16, left padding 16 bytes: no shifts at all
+    ConvShape(2, 3, 11, 40, 40, 3, 3, 2, 1, "bf16", "f32"),      # S*C = 9, padding 6 bytes, stride 2
+    ConvShape(1, 2, 12, 36, 70, 5, 5, 1, 2, "f16", "f32"),       # S*C = 10, padding 8 bytes, two filter tiles
+    ConvShape(1, 6, 9, 20, 16, 3, 5, 1, 2, "bf16", "bf16"),      # S*C = 30, padding 24 bytes
+    ConvShape(1, 3, 14, 16, 64, 9, 3, 2, 1, "bf16", "f32"),      # 9 filter rows: more than one staging round
+    ConvShape(1, 3, 33, 272, 64, 7, 7, 2, 3, "bf16", "f32"),     # wide image: more than one round of row vectors
+    ConvShape(3, 4, 8, 8, 9, 3, 7, 1, 0, "f16", "f16"),          # S*C = 28, no padding, 9 filters
+    ConvShape(1, 3, 224, 224, 64, 7, 7, 2, 3, "bf16", "bf16"),   # the ResNet stem itself
+]
+
+
+@pytest.mark.parametrize("rows_per_tile", [1, 2, 4])
+def test_row_tile_alignments(torch, rows_per_tile):
+    from tests import helpers
+    tenants = [helpers.Tenant(s, synth.gen_input(91, t, 0, s), synth.gen_weight(91, t, 0, s)) for t, s in enumerate(ROW_SHAPES)]
+    plan = helpers.plan_for(tenants, tile_cfg=7, rows_per_tile=rows_per_tile)
+    for t in range(len(tenants)):
+        ti = sc.st_conv_plan_tenant_info(plan, t)
+        assert ti.row_tiled == 1 and ti.rows_per_tile == rows_per_tile, f"tenant {t} did not take the row tile"
+    sc.st_conv_run(plan)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"row[{i}] {t.shape} rows_per_tile={rows_per_tile}")
+
+
 def test_auto_plan_small(torch):
     from tests import helpers
     _run_small(torch, helpers)
