@@ -32,6 +32,7 @@ constexpr TileShape kTileShapes[kNumTileCfgs] = {
 };
 constexpr int smem_need(int c) { return 2 * (kTileShapes[c].MT + kTileShapes[c].NT) * (kTileShapes[c].KB + 16); }
 constexpr int kSmemBytes = 73728;  // LDS per workgroup: the largest of the family (checked per tile)
+constexpr int kRowStageBytes = 18432;   // row tile: LDS set aside for the epilogue's transposition buffer
 // tile shapes that also exist as element-wise-gather kernels (channel count not a multiple of the
 // 16-byte vector width); the planner maps such tenants onto one of them
 constexpr bool kGenericCfg[kNumTileCfgs] = {false, true, false, true, false, false, false};

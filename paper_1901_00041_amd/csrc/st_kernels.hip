@@ -150,7 +150,7 @@ constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every bu
 // im2col row m0 and first filter n0; rows at or past m_end are not stored.
 // The transposition buffer `smem` holds MT/PASSES pixel rows; with PASSES > 1 the tile is written out in
 // that many slices of consecutive pixel rows.
-template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, class Acc>
+template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, int CAP = kSmemBytes, class Acc>
 __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
                                               int wn0, int lrow, int lk, int tid, char* smem, uint64_t* prof = nullptr) {
   constexpr int NG = (MF == 32) ? 4 : 1;
@@ -158,13 +158,57 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
   const bool has_res = (T.epilogue & ST_EPI_RESIDUAL) != 0u;
   const int Kf = T.K;
   const bool vec4 = (Kf & 3) == 0;
-  if ((Kf & 7) == 0) {
+  if ((Kf & 7) == 0 && T.out_dtype != ST_DT_F32 && !has_res) {
+    // 16-bit output without a residual: ReLU and the rounding are applied to the accumulators, and the
+    // transposition buffer holds the finished 16-bit values, [pixel][filter], the whole tile at once.  Every
+    // lane then moves 16 bytes of one output row from LDS to memory.
+    constexpr int PITCHB = NT * 2 + 16;   // bytes per pixel row; the pad spreads the 8-byte writes of 8 pixels over the banks
+    static_assert(MT * PITCHB <= CAP, "16-bit output tile does not fit the transposition buffer");
+    const bool isbf = (T.out_dtype == ST_DT_BF16);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
+    __syncthreads();                // the buffer (operands, split-K flag, or the previous tile) is no longer read
+#pragma unroll
+    for (int i = 0; i < BM; ++i)
+#pragma unroll
+      for (int j = 0; j < BN; ++j)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const int row = wm0 + i * MF + lrow;
+          const int chl = wn0 + j * MF + ((MF == 32) ? (8 * g + 4 * lk) : (4 * lk));
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[e] = acc[i][j][4 * g + e];
+            if (relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+          }
+          uint2 pk;
+          pk.x = isbf ? ((uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16))
+                      : ((uint32_t)f32_to_f16_bits(v[0]) | ((uint32_t)f32_to_f16_bits(v[1]) << 16));
+          pk.y = isbf ? ((uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16))
+                      : ((uint32_t)f32_to_f16_bits(v[2]) | ((uint32_t)f32_to_f16_bits(v[3]) << 16));
+          *(uint2*)(smem + row * PITCHB + chl * 2) = pk;
+        }
+    __syncthreads();
+    if (prof && tid == 0) prof[7] = __builtin_readcyclecounter();
+    constexpr int NV = NT / 8;
+    constexpr int IT = (MT * NV + kThreads - 1) / kThreads;
+#pragma unroll
+    for (int u = 0; u < IT; ++u) {
+      const int v = u * kThreads + tid;
+      const int row = v / NV, cv = v % NV;
+      const int m = m0 + row, ch = n0 + cv * 8;
+      const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
+      const uint32_t off = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
+      const u32x4 d = *(const u32x4*)(smem + (row < MT ? row : 0) * PITCHB + cv * 16);
+      __builtin_amdgcn_raw_buffer_store_b128(d, ry, (int)off, 0, 0);
+    }
+  } else if ((Kf & 7) == 0) {
     // Transpose through LDS: accumulators go to an fp32 [pixel][filter] tile, then every lane handles 16
     // bytes of one output row, so residual loads and output stores are whole contiguous rows.
     constexpr int PITCH = NT + 4;   // floats; the pad keeps the 16-byte writes of 16 pixels on distinct banks
     constexpr int MP = MT / PASSES; // pixel rows per slice
     static_assert(MT % PASSES == 0 && MP % MF == 0, "slices must hold whole MFMA blocks");
-    static_assert(MP * PITCH * 4 <= kSmemBytes, "output tile does not fit the LDS allocation");
+    static_assert(MP * PITCH * 4 <= CAP, "output tile does not fit the transposition buffer");
     float* sC = (float*)smem;
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(T.y, T.y_bytes);
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(has_res ? T.res : T.y, T.y_bytes);
@@ -680,7 +724,9 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
   const int RT = T.rows_per_tile;                    // output rows per work item (1..kRowsPerTile)
   constexpr int EPI_PASSES = 2;
-  constexpr int kStageBytes = (MT / EPI_PASSES) * (NT + 4) * 4;      // epilogue transposition buffer
+  // epilogue transposition buffer: the larger of half a tile of fp32 values and a whole tile of 16-bit ones
+  constexpr int kStageBytes = kRowStageBytes;
+  static_assert(kStageBytes >= (MT / EPI_PASSES) * (NT + 4) * 4 && kStageBytes >= MT * (NT * 2 + 16), "row tile stage buffer");
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
   const int tid = threadIdx.x;
@@ -860,7 +906,7 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
     };
     if (nh > 1) k_loop(std::integral_constant<int, 2>{}); else k_loop(std::integral_constant<int, 1>{});
     const int mrow = (n * P + p0 + rt) * Q;
-    tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
+    tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES, kStageBytes>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
   }
   if (prof && tid == 0) {
     prof[2] = prof[3] = __builtin_readcyclecounter();

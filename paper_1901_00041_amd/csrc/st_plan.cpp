@@ -143,7 +143,7 @@ static bool row_tile_ok(const st_conv_desc& d) {
   const int Q = (d.W + 2 * d.pad - d.S) / d.stride + 1;
   const int reach = (Q - 1) * d.stride * d.C * 2 + 64;             // furthest byte a pixel operand read touches
   if (reach > pitch) return false;
-  const int64_t stage = (kTileShapes[kRowCfg].MT / 2) * (kTileShapes[kRowCfg].NT + 4) * 4;   // epilogue buffer
+  const int64_t stage = kRowStageBytes;                                                       // epilogue buffer
   const int64_t rows = d.R + d.stride * (kRowsPerTile - 1);
   return stage + rows * pitch + (int64_t)kTileShapes[kRowCfg].NT * d.R * 64 <= kSmemBytes;
 }
