@@ -1,5 +1,8 @@
 """Configuration 5: several tenants, each running a ResNet-50-shaped stack of 53 convolution layers,
 scheduled layer by layer: step s of every tenant goes into one fused launch (one cached plan per step).
+Consecutive steps that do not depend on each other (a block's projection conv and its first 1x1 conv both
+read the block input) are co-scheduled: the fused policy issues them as one launch over both steps'
+descriptors.
 
 Data flow per tenant (no batch-norm): stem conv + ReLU, 3x3/2 max-pool, then per bottleneck
 a = ReLU(conv1(x)), b = ReLU(conv2(a)), out = ReLU(conv3(b) + shortcut), shortcut = x or proj(x).
@@ -20,7 +23,7 @@ from . import synth
 
 class ResNetStack:
     def __init__(self, n_tenants: int = 8, cfg: int = 5, batch: int = 1, image: int = 224, seeded_weights: bool = True,
-                 plan_opts=None):
+                 plan_opts=None, co_schedule: bool = True):
         import torch
         self.torch = torch
         self.n_tenants, self.cfg = n_tenants, cfg
@@ -57,6 +60,7 @@ class ResNetStack:
         # one plan per step
         self.plans, t_plan = [], []
         self.flops = self.bytes = self.n_items = 0
+        step_descs = []
         for st in self.steps:
             s = st.shape
             epi = (sc.ST_EPI_RELU if st.relu else 0) | (sc.ST_EPI_RESIDUAL if st.res is not None else 0)
@@ -64,6 +68,7 @@ class ResNetStack:
                                   self.buf[st.src][t], self.weights[st.index][t], self.buf[st.dst][t],
                                   self.buf[st.res][t] if st.res is not None else None, epi)
                      for t in range(n_tenants)]
+            step_descs.append(descs)
             t0 = time.perf_counter()
             plan = sc.st_conv_plan(descs, plan_opts)
             t_plan.append((time.perf_counter() - t0) * 1e6)
@@ -73,10 +78,47 @@ class ResNetStack:
             self.bytes += int(info.bytes)
             self.n_items += int(info.n_items)
         self.plan_build_us = float(np.median(t_plan))
-        self.n_launches = len(self.steps)
+        # groups of consecutive, mutually independent steps; each group of more than one step gets a plan of
+        # its own over all its descriptors
+        self.groups: List[List[int]] = []
+        for st in self.steps:
+            if co_schedule and self.groups and self._independent(self.groups[-1], st):
+                self.groups[-1].append(st.index)
+            else:
+                self.groups.append([st.index])
+        self.group_plans = []
+        for g in self.groups:
+            if len(g) == 1:
+                self.group_plans.append(self.plans[g[0]])
+            else:
+                self.group_plans.append(sc.st_conv_plan([d for i in g for d in step_descs[i]], plan_opts))
+        self.n_items = sum(int(sc.st_conv_plan_info(p).n_items) for p in self.group_plans)
+        self.n_launches = len(self.groups)
         self._streams = [torch.cuda.Stream() for _ in range(n_tenants)]
 
+    def _independent(self, group: List[int], st) -> bool:
+        """True when step `st` neither reads what a step of the group writes nor writes what one reads or writes."""
+        for i in group:
+            g = self.steps[i]
+            if g.pool_after or st.pool_after:
+                return False
+            if st.src in (g.dst,) or (st.res is not None and st.res == g.dst):
+                return False
+            if st.dst in (g.src, g.dst) or (g.res is not None and st.dst == g.res):
+                return False
+        return True
+
     # ---- execution -----------------------------------------------------------------------------------
+    def run_group(self, gi: int, stream=None) -> None:
+        """One fused launch over every tenant's descriptors of every step of group gi."""
+        sc.st_conv_run(self.group_plans[gi], stream)
+        for i in self.groups[gi]:
+            st = self.steps[i]
+            if st.pool_after:
+                s = st.shape
+                sc.st_maxpool_nhwc(self.buf[st.dst], self.buf[st.pool_dst], self.n_tenants * s.N, s.P, s.Q, s.K, 3, 2, 1,
+                                   "bf16", stream)
+
     def run_step(self, i: int, policy: str = "fused", stream=None) -> None:
         st = self.steps[i]
         if policy == "fused":
@@ -92,6 +134,10 @@ class ResNetStack:
                                "bf16", stream)
 
     def run(self, policy: str = "fused", stream=None) -> None:
+        if policy == "fused":
+            for gi in range(len(self.groups)):
+                self.run_group(gi, stream)
+            return
         for i in range(len(self.steps)):
             self.run_step(i, policy, stream)
 
