@@ -8,6 +8,7 @@ namespace st {
 
 constexpr int kThreads = 256;      // workgroup size of every conv kernel: 4 wavefronts of 64
 constexpr int kNumCUs = 256;       // MI355X
+constexpr int kNumXCDs = 8;        // workgroup b of a launch runs on XCD b mod 8
 constexpr int kProfSlots = 8;      // 64-bit stamps per work item in a profiled launch
 
 // Tile family.  MT = output pixels (rows of the im2col matrix), NT = filters per workgroup tile.

@@ -148,6 +148,42 @@ static bool row_tile_ok(const st_conv_desc& d) {
   return stage + rows * pitch + (int64_t)kTileShapes[kRowCfg].NT * d.R * 64 <= kSmemBytes;
 }
 
+// XCD-aware placement.  The hardware hands workgroup b of a launch to XCD b mod 8, and each XCD has an L2 of
+// its own, so work items that read the same slice of an operand should sit at positions that are equal
+// mod 8.  Items are grouped by the operand slice whose re-reads would cost more (xcd_group_by: 1 = weights,
+// group = (filter tile, K slice), shared by the pixel tiles; 2 = activations, group = (pixel tile, K slice),
+// shared by the filter tiles); group g prefers XCD g mod 8.  The items of a run are dealt out position by
+// position: position q (XCD (phase + q) mod 8) takes the next item that prefers this XCD, or, when none is
+// left, the next item of the XCD with the most items left (lowest XCD on ties).
+static void xcd_arrange(st_work_item* items, int64_t n, int phase, const st_tenant_info& ti) {
+  if (ti.xcd_group_by == 0 || n < 2) return;
+  std::vector<st_work_item> bucket[kNumXCDs];
+  size_t head[kNumXCDs] = {};
+  for (int64_t i = 0; i < n; ++i) {
+    const st_work_item& it = items[i];
+    const int64_t g = (int64_t)(ti.xcd_group_by == 1 ? it.tile_n : it.tile_m) * ti.split_k + it.k_split_idx;
+    bucket[g % kNumXCDs].push_back(it);
+  }
+  for (int64_t q = 0; q < n; ++q) {
+    int x = (int)((phase + q) % kNumXCDs);
+    if (head[x] == bucket[x].size()) {
+      size_t best = 0;
+      for (int c = 0; c < kNumXCDs; ++c)
+        if (bucket[c].size() - head[c] > best) { best = bucket[c].size() - head[c]; x = c; }
+    }
+    items[q] = bucket[x][head[x]++];
+  }
+}
+
+static int xcd_group_choice(const st_conv_desc& d, const st_tenant_info& ti) {
+  const int64_t es = elem_size(d.in_dtype);
+  const int64_t w_bytes = ti.Ngemm * ti.Kgemm * es, x_bytes = (int64_t)d.N * d.C * d.H * d.W * es;
+  const int64_t save_w = (std::min<int64_t>(ti.tiles_m, kNumXCDs) - 1) * w_bytes;
+  const int64_t save_x = (std::min<int64_t>(ti.tiles_n, kNumXCDs) - 1) * x_bytes;
+  if (save_w <= 0 && save_x <= 0) return 0;
+  return save_w >= save_x ? 1 : 2;
+}
+
 static Option make_row_option(const st_conv_desc& d, int rows_per_tile) {
   Option o;
   o.rows_per_tile = rows_per_tile;
@@ -376,6 +412,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       ti.k_steps_per_split = op.steps_per_split;
       ti.item_begin = fused_total;
       ti.item_count = (int64_t)ti.tiles_m * ti.tiles_n * op.split;
+      ti.xcd_group_by = xcd_group_choice(descs[t], ti);
       fused_total += ti.item_count;
     }
     if (fused_total >= ((int64_t)1 << 31)) {
@@ -400,6 +437,12 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
     }
     // fused order: longest work item first, so that short items fill the tail of the launch
     p->items_fused = p->items_tenant;
+    // each tenant's launch of its own (the baselines) starts at its first item: XCD = position in the range, mod 8
+    for (int t = 0; t < n_tenants; ++t) {
+      const st_tenant_info& ti = p->info[t];
+      xcd_arrange(p->items_tenant.data() + ti.item_begin, ti.item_count, 0, ti);
+    }
+    if (o.order == 1) p->items_fused = p->items_tenant;
     if (o.order == 0) {
       auto cost = [&](const st_work_item& it) {
         const st_tenant_info& ti = p->info[it.tenant];
@@ -409,6 +452,13 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       };
       std::stable_sort(p->items_fused.begin(), p->items_fused.end(),
                        [&](const st_work_item& a, const st_work_item& b) { return cost(a) > cost(b); });
+      // within every run of one tenant's items, place the items that read the same operand slice on one XCD
+      for (size_t b = 0; b < p->items_fused.size();) {
+        size_t e = b + 1;
+        while (e < p->items_fused.size() && p->items_fused[e].tenant == p->items_fused[b].tenant) ++e;
+        xcd_arrange(p->items_fused.data() + b, (int64_t)(e - b), (int)(b % kNumXCDs), p->info[p->items_fused[b].tenant]);
+        b = e;
+      }
     }
     // device records
     for (int t = 0; t < n_tenants; ++t) {

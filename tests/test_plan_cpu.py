@@ -59,8 +59,40 @@ def test_config_totals_match_generator(cfg):
         assert (ti.M, ti.Ngemm, ti.Kgemm) == s.gemm and (ti.P, ti.Q) == (s.P, s.Q)
 
 
-def _expected_tenant_major(plan, n_tenants):
-    """Independent enumeration: tenant, pixel tile, filter tile, K slice, from the per-tenant summary only."""
+def _xcd_group_by(shape, ti):
+    """Which operand's re-reads the placement avoids: the slice shared by more tiles, weighted by its size."""
+    es = 4 if shape.dtype == "f32" else 2
+    w_bytes = ti.Ngemm * ti.Kgemm * es
+    x_bytes = shape.N * shape.C * shape.H * shape.W * es
+    save_w = (min(ti.tiles_m, 8) - 1) * w_bytes
+    save_x = (min(ti.tiles_n, 8) - 1) * x_bytes
+    if save_w <= 0 and save_x <= 0:
+        return 0
+    return 1 if save_w >= save_x else 2
+
+
+def _xcd_deal(rows, phase, mode, split_k):
+    """The placement rule restated: rows (tenant, k, tile_m, tile_n, 0) in nested order are dealt to launch
+    positions; position q (XCD (phase+q) % 8) takes the next row whose group prefers that XCD, else the next
+    row of the XCD with most rows left (lowest XCD on ties)."""
+    if mode == 0 or len(rows) < 2:
+        return list(rows)
+    buckets = [[] for _ in range(8)]
+    for r in rows:
+        g = (r[3] if mode == 1 else r[2]) * split_k + r[1]
+        buckets[g % 8].append(r)
+    out = []
+    for q in range(len(rows)):
+        x = (phase + q) % 8
+        if not buckets[x]:
+            x = max(range(8), key=lambda c: (len(buckets[c]), -c))
+        out.append(buckets[x].pop(0))
+    return out
+
+
+def _expected_tenant_major(plan, n_tenants, shapes=None):
+    """Independent enumeration from the per-tenant summary only: per tenant the nested order pixel tile,
+    filter tile, K slice, dealt to XCDs with each tenant's own launch starting at its first item."""
     rows = []
     for t in range(n_tenants):
         ti = sc.st_conv_plan_tenant_info(plan, t)
@@ -75,10 +107,10 @@ def _expected_tenant_major(plan, n_tenants):
         assert ti.k_steps_per_split == -(-ti.k_steps // ti.split_k)
         assert (ti.split_k - 1) * ti.k_steps_per_split < ti.k_steps, "an empty K slice"
         assert ti.item_begin == len(rows) and ti.item_count == ti.tiles_m * ti.tiles_n * ti.split_k
-        for tm in range(ti.tiles_m):
-            for tn in range(ti.tiles_n):
-                for s in range(ti.split_k):
-                    rows.append((t, s, tm, tn, 0))
+        mine = [(t, s, tm, tn, 0) for tm in range(ti.tiles_m) for tn in range(ti.tiles_n) for s in range(ti.split_k)]
+        if shapes is not None:
+            assert ti.xcd_group_by == _xcd_group_by(shapes[t], ti)
+        rows.extend(_xcd_deal(mine, 0, ti.xcd_group_by, ti.split_k))
     return np.array(rows, dtype=np.int64).reshape(-1, 5)
 
 
@@ -91,7 +123,7 @@ def _as_rows(items):
 def test_work_lists_bit_exact(cfg, opts):
     shapes = synth.config_shapes(cfg)
     p = _host_plan(shapes, **opts)
-    want = _expected_tenant_major(p, len(shapes))
+    want = _expected_tenant_major(p, len(shapes), shapes)
     tenant_major = _as_rows(sc.st_conv_plan_worklist(p, 1))
     assert np.array_equal(tenant_major, want)
     fused = _as_rows(sc.st_conv_plan_worklist(p, 0))
@@ -119,6 +151,30 @@ def test_work_lists_bit_exact(cfg, opts):
     # determinism: the same descriptors give the same lists
     p2 = _host_plan(shapes, **opts)
     assert np.array_equal(_as_rows(sc.st_conv_plan_worklist(p2, 0)), fused)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_fused_list_keeps_operand_slices_on_one_xcd(cfg):
+    """Workgroup b of a launch runs on XCD b mod 8.  For every tenant whose items form one run of the fused list
+    and whose sharing groups divide evenly among the XCDs (a multiple of 8 groups, or a divisor of 8), the items
+    that read one operand slice sit on as few XCDs as an even spread of the work allows: 1, or 8 / groups."""
+    shapes = synth.config_shapes(cfg)
+    p = _host_plan(shapes)
+    fused = _as_rows(sc.st_conv_plan_worklist(p, 0))
+    checked = 0
+    for t in range(len(shapes)):
+        ti = sc.st_conv_plan_tenant_info(p, t)
+        pos = np.nonzero(fused[:, 0] == t)[0]
+        n_groups = (ti.tiles_n if ti.xcd_group_by == 1 else ti.tiles_m) * ti.split_k
+        if ti.xcd_group_by == 0 or len(pos) != pos[-1] - pos[0] + 1 or (n_groups % 8 != 0 and 8 % n_groups != 0):
+            continue
+        bound = 1 if n_groups % 8 == 0 else 8 // n_groups
+        key = fused[pos, 3] if ti.xcd_group_by == 1 else fused[pos, 2]
+        group = key * ti.split_k + fused[pos, 1]
+        for g in np.unique(group):
+            assert len(set((pos[group == g] % 8).tolist())) <= bound, f"tenant {t} group {g} spans more than {bound} XCDs"
+        checked += 1
+    assert checked > 0
 
 
 def test_fused_order_longest_first():
