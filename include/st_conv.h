@@ -164,6 +164,33 @@ st_status st_conv_run_plans_space_only(const st_plan* const* plans, int32_t n_pl
 st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const void* x, const void* w, void* y,
                               const void* residual);
 
+/* All tenants' pointers at once, from descs[t].x/w/y/residual (everything else in descs is ignored; the
+ * plan keeps its shapes).  Nothing happens when no pointer differs from the plan's current ones.
+ * Otherwise the device table is updated by one copy ordered on hip_stream, from pinned memory the plan
+ * owns: runs queued on that stream before the call still see the old pointers, runs queued after it the
+ * new ones.  Runs of this plan on other streams must not overlap the call. */
+st_status st_conv_plan_rebind_all(st_plan* plan, const st_conv_desc* descs, int32_t n_tenants, void* hip_stream);
+
+/* Plan cache for dynamically arriving work (Section 4: the scheduler merges whichever kernels are ready,
+ * and caches super-kernels so that the cost of scheduling is paid once per distinct merge).  Plans are
+ * keyed by the descriptors in order, everything but the four pointers (a NULL and a non-NULL residual
+ * differ).  st_plan_cache_get returns the cached plan rebound to the given pointers (as
+ * st_conv_plan_rebind_all on hip_stream), or builds one with the cache's options (device allocation,
+ * as st_conv_plan) and keeps it; when the cache is full the least recently used plan is destroyed first
+ * (which waits for the device).  The returned plan belongs to the cache and stays valid until it is
+ * evicted or the cache destroyed.  *out_hit (optional) receives 1 for a cached plan, 0 for a new one.
+ * Not thread-safe. */
+typedef struct st_plan_cache st_plan_cache;
+typedef struct st_plan_cache_stats {
+  int64_t hits, misses, evictions;
+  int32_t size, capacity;
+} st_plan_cache_stats;
+st_status st_plan_cache_create(int32_t capacity, const st_plan_opts* opts, st_plan_cache** out_cache);
+st_status st_plan_cache_get(st_plan_cache* cache, const st_conv_desc* descs, int32_t n_tenants, void* hip_stream,
+                            st_plan** out_plan, int32_t* out_hit);
+st_status st_plan_cache_get_stats(const st_plan_cache* cache, st_plan_cache_stats* out);
+void st_plan_cache_destroy(st_plan_cache* cache);
+
 /* Introspection (used by the bit-exact work-list tests and by reports). */
 st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out);
 st_status st_conv_plan_tenant_info(const st_plan* plan, int32_t tenant, st_tenant_info* out);

@@ -53,6 +53,12 @@ struct st_plan {
   char* d_workspace = nullptr;              // all tenants' split-K partials, then all counters
   hipEvent_t ev_fork = nullptr;
   std::vector<hipEvent_t> ev_join;          // one per stream slot used by space-only
+  // pinned staging slots for stream-ordered uploads of the tenant table (st_conv_plan_rebind_all)
+  static constexpr int kStageSlots = 4;
+  TenantDev* h_stage[kStageSlots] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev_stage[kStageSlots] = {nullptr, nullptr, nullptr, nullptr};
+  bool stage_used[kStageSlots] = {false, false, false, false};
+  int stage_next = 0;
 };
 
 
@@ -287,6 +293,12 @@ static void choose_all(const std::vector<std::vector<Option>>& opts, int slots, 
 
 static void destroy_device(st_plan* p) {
   if (p->d_tenants) (void)hipFree(p->d_tenants);
+  for (int i = 0; i < st_plan::kStageSlots; ++i) {
+    if (p->h_stage[i]) (void)hipHostFree(p->h_stage[i]);
+    if (p->ev_stage[i]) (void)hipEventDestroy(p->ev_stage[i]);
+    p->h_stage[i] = nullptr;
+    p->ev_stage[i] = nullptr;
+  }
   if (p->d_items_fused) (void)hipFree(p->d_items_fused);
   if (p->d_items_tenant) (void)hipFree(p->d_items_tenant);
   if (p->d_workspace) (void)hipFree(p->d_workspace);
@@ -625,6 +637,154 @@ extern "C" st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const vo
   st_conv_desc& d = plan->descs[tenant];
   d.x = T.x; d.w = T.w; d.y = T.y; d.residual = T.res;
   return ST_OK;
+}
+
+extern "C" st_status st_conv_plan_rebind_all(st_plan* plan, const st_conv_desc* descs, int32_t n_tenants, void* hip_stream) {
+  if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");
+  if (n_tenants != (int32_t)plan->tenants.size()) return fail(ST_ERR_INVALID_ARG, "n_tenants differs from the plan's");
+  if (n_tenants > 0 && !descs) return fail(ST_ERR_INVALID_ARG, "descs is NULL");
+  bool changed = false;
+  for (int t = 0; t < n_tenants; ++t) {
+    const st_conv_desc& d = descs[t];
+    const TenantDev& T = plan->tenants[t];
+    if (!d.x || !d.w || !d.y) return fail(ST_ERR_INVALID_ARG, "tenant %d: x, w and y must be non-NULL", t);
+    if (d.y == d.x || d.y == d.w) return fail(ST_ERR_INVALID_ARG, "tenant %d: y must not alias x or w", t);
+    if ((T.epilogue & ST_EPI_RESIDUAL) && !d.residual)
+      return fail(ST_ERR_INVALID_ARG, "tenant %d: the plan adds a residual but none is given", t);
+    changed |= d.x != T.x || d.w != T.w || d.y != T.y || ((T.epilogue & ST_EPI_RESIDUAL) && d.residual != T.res);
+  }
+  if (!changed) return ST_OK;
+  for (int t = 0; t < n_tenants; ++t) {
+    const st_conv_desc& d = descs[t];
+    TenantDev& T = plan->tenants[t];
+    T.x = d.x; T.w = d.w; T.y = d.y;
+    if (T.epilogue & ST_EPI_RESIDUAL) T.res = d.residual;
+    st_conv_desc& mine = plan->descs[t];
+    mine.x = T.x; mine.w = T.w; mine.y = T.y; mine.residual = T.res;
+  }
+  if (plan->host_only || n_tenants == 0) return ST_OK;
+  // stream-ordered upload from a pinned slot; a slot is reused only after the copy that read it has finished
+  const int slot = plan->stage_next;
+  plan->stage_next = (slot + 1) % st_plan::kStageSlots;
+  const size_t bytes = plan->tenants.size() * sizeof(TenantDev);
+  if (!plan->h_stage[slot]) {
+    ST_HIP(hipHostMalloc((void**)&plan->h_stage[slot], bytes, hipHostMallocDefault));
+    ST_HIP(hipEventCreateWithFlags(&plan->ev_stage[slot], hipEventDisableTiming));
+  }
+  if (plan->stage_used[slot]) ST_HIP(hipEventSynchronize(plan->ev_stage[slot]));
+  std::memcpy(plan->h_stage[slot], plan->tenants.data(), bytes);
+  ST_HIP(hipMemcpyAsync(plan->d_tenants, plan->h_stage[slot], bytes, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+  ST_HIP(hipEventRecord(plan->ev_stage[slot], (hipStream_t)hip_stream));
+  plan->stage_used[slot] = true;
+  return ST_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// plan cache: the ready set of tenants changes from step to step; plans are keyed by everything in the
+// descriptors except the pointers
+// ---------------------------------------------------------------------------------------------------
+struct st_plan_cache {
+  struct Entry {
+    std::vector<int32_t> key;
+    st_plan* plan = nullptr;
+    uint64_t last_use = 0;
+  };
+  std::vector<Entry> entries;
+  st_plan_opts opts;
+  int capacity = 0;
+  uint64_t clock = 0;
+  int64_t hits = 0, misses = 0, evictions = 0;
+};
+
+static void cache_key(const st_conv_desc* descs, int32_t n, std::vector<int32_t>* key) {
+  key->clear();
+  key->reserve((size_t)n * 14 + 1);
+  key->push_back(n);
+  for (int t = 0; t < n; ++t) {
+    const st_conv_desc& d = descs[t];
+    const int32_t f[14] = {d.N, d.C, d.H, d.W, d.K, d.R, d.S, d.stride, d.pad, d.in_dtype, d.out_dtype, d.layout,
+                           (int32_t)d.epilogue, d.residual ? 1 : 0};
+    key->insert(key->end(), f, f + 14);
+  }
+}
+
+extern "C" st_status st_plan_cache_create(int32_t capacity, const st_plan_opts* opts, st_plan_cache** out_cache) {
+  if (!out_cache) return fail(ST_ERR_INVALID_ARG, "out_cache is NULL");
+  *out_cache = nullptr;
+  if (capacity < 1) return fail(ST_ERR_INVALID_ARG, "capacity must be at least 1");
+  st_plan_cache* c = new (std::nothrow) st_plan_cache();
+  if (!c) return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  std::memset(&c->opts, 0, sizeof(c->opts));
+  if (opts) c->opts = *opts;
+  c->capacity = capacity;
+  *out_cache = c;
+  return ST_OK;
+}
+
+extern "C" st_status st_plan_cache_get(st_plan_cache* cache, const st_conv_desc* descs, int32_t n_tenants, void* hip_stream,
+                                       st_plan** out_plan, int32_t* out_hit) {
+  if (!cache || !out_plan) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  *out_plan = nullptr;
+  if (n_tenants < 0 || (n_tenants > 0 && !descs)) return fail(ST_ERR_INVALID_ARG, "descs is NULL or n_tenants negative");
+  std::vector<int32_t> key;
+  try {
+    cache_key(descs, n_tenants, &key);
+  } catch (const std::bad_alloc&) {
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  ++cache->clock;
+  for (st_plan_cache::Entry& e : cache->entries) {
+    if (e.key == key) {
+      st_status s = st_conv_plan_rebind_all(e.plan, descs, n_tenants, hip_stream);
+      if (s != ST_OK) return s;
+      e.last_use = cache->clock;
+      ++cache->hits;
+      if (out_hit) *out_hit = 1;
+      *out_plan = e.plan;
+      return ST_OK;
+    }
+  }
+  st_plan* plan = nullptr;
+  st_status s = st_conv_plan(descs, n_tenants, &cache->opts, &plan);
+  if (s != ST_OK) return s;
+  ++cache->misses;
+  if ((int)cache->entries.size() >= cache->capacity) {
+    size_t victim = 0;
+    for (size_t i = 1; i < cache->entries.size(); ++i)
+      if (cache->entries[i].last_use < cache->entries[victim].last_use) victim = i;
+    st_conv_plan_destroy(cache->entries[victim].plan);
+    cache->entries.erase(cache->entries.begin() + (long)victim);
+    ++cache->evictions;
+  }
+  try {
+    st_plan_cache::Entry e;
+    e.key.swap(key);
+    e.plan = plan;
+    e.last_use = cache->clock;
+    cache->entries.push_back(std::move(e));
+  } catch (const std::bad_alloc&) {
+    st_conv_plan_destroy(plan);
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  if (out_hit) *out_hit = 0;
+  *out_plan = plan;
+  return ST_OK;
+}
+
+extern "C" st_status st_plan_cache_get_stats(const st_plan_cache* cache, st_plan_cache_stats* out) {
+  if (!cache || !out) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  out->hits = cache->hits;
+  out->misses = cache->misses;
+  out->evictions = cache->evictions;
+  out->size = (int32_t)cache->entries.size();
+  out->capacity = cache->capacity;
+  return ST_OK;
+}
+
+extern "C" void st_plan_cache_destroy(st_plan_cache* cache) {
+  if (!cache) return;
+  for (st_plan_cache::Entry& e : cache->entries) st_conv_plan_destroy(e.plan);
+  delete cache;
 }
 
 extern "C" st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out) {

@@ -19,7 +19,8 @@ ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
-           "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
+           "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
+           "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
@@ -63,6 +64,11 @@ class st_plan_info(ctypes.Structure):
                 ("flops", ctypes.c_int64), ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
 
 
+class st_plan_cache_stats(ctypes.Structure):
+    _fields_ = [("hits", ctypes.c_int64), ("misses", ctypes.c_int64), ("evictions", ctypes.c_int64),
+                ("size", ctypes.c_int32), ("capacity", ctypes.c_int32)]
+
+
 class StError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -89,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.st_conv_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
         L.st_conv_plan_rebind.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.st_conv_plan_rebind_all.argtypes = [vp, P(st_conv_desc), i32, vp]
+        L.st_plan_cache_create.argtypes = [i32, P(st_plan_opts), P(vp)]
+        L.st_plan_cache_get.argtypes = [vp, P(st_conv_desc), i32, vp, P(vp), P(i32)]
+        L.st_plan_cache_get_stats.argtypes = [vp, P(st_plan_cache_stats)]
+        L.st_plan_cache_destroy.argtypes = [vp]
+        L.st_plan_cache_destroy.restype = None
         L.st_conv_run_plans_time_only.argtypes = [P(vp), i32, vp]
         L.st_conv_run_plans_space_only.argtypes = [P(vp), i32, P(vp), i32]
         L.st_conv_plan_info.argtypes = [vp, P(st_plan_info)]
@@ -107,7 +119,8 @@ def lib() -> ctypes.CDLL:
         L.st_last_error_message.restype = ctypes.c_char_p
         for name in ("st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_plans_time_only",
                      "st_conv_run_plans_space_only", "st_conv_run_time_only", "st_conv_run_space_only",
-                     "st_conv_plan_rebind", "st_conv_plan_info", "st_conv_plan_tenant_info",
+                     "st_conv_plan_rebind", "st_conv_plan_rebind_all", "st_plan_cache_create", "st_plan_cache_get",
+                     "st_plan_cache_get_stats", "st_conv_plan_info", "st_conv_plan_tenant_info",
                      "st_conv_plan_worklist", "st_tile_shape", "st_tile_count",
                      "st_maxpool_nhwc", "st_launch_empty", "st_launch_copy"):
             getattr(L, name).restype = i32
@@ -160,6 +173,17 @@ class Plan:
             except Exception:      # interpreter shutdown
                 pass
             self.handle = None
+
+
+class BorrowedPlan(Plan):
+    """A plan handle owned by someone else (a plan cache): never destroyed from here."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+        self._keep = None
+
+    def destroy(self):
+        self.handle = None
 
 
 def st_conv_plan(descs: Sequence[st_conv_desc], opts: Optional[st_plan_opts] = None, keep=None) -> Plan:
@@ -226,6 +250,50 @@ def st_conv_plan_rebind(plan: Plan, tenant: int, x=None, w=None, y=None, residua
            "st_conv_plan_rebind")
     if plan._keep is not None:
         plan._keep.append((x, w, y, residual))
+
+
+def st_conv_plan_rebind_all(plan: Plan, descs: Sequence[st_conv_desc], stream=None, keep=None) -> None:
+    n = len(descs)
+    arr = (st_conv_desc * max(n, 1))(*descs)
+    _check(lib().st_conv_plan_rebind_all(plan.handle, arr, n, _stream(stream)), "st_conv_plan_rebind_all")
+    if keep is not None and plan._keep is not None:
+        plan._keep.append(keep)
+
+
+class PlanCache:
+    """Owns an st_plan_cache*.  Plans returned by get() belong to the cache: they are plain handles wrapped
+    without ownership, valid until evicted or until the cache is destroyed."""
+
+    def __init__(self, capacity: int, opts: Optional[st_plan_opts] = None):
+        out = ctypes.c_void_p()
+        _check(lib().st_plan_cache_create(capacity, ctypes.byref(opts) if opts is not None else None, ctypes.byref(out)),
+               "st_plan_cache_create")
+        self.handle = out.value
+
+    def get(self, descs: Sequence[st_conv_desc], stream=None):
+        """Returns (plan, hit)."""
+        n = len(descs)
+        arr = (st_conv_desc * max(n, 1))(*descs)
+        out, hit = ctypes.c_void_p(), ctypes.c_int32()
+        _check(lib().st_plan_cache_get(self.handle, arr, n, _stream(stream), ctypes.byref(out), ctypes.byref(hit)),
+               "st_plan_cache_get")
+        return BorrowedPlan(out.value), bool(hit.value)
+
+    def stats(self) -> st_plan_cache_stats:
+        out = st_plan_cache_stats()
+        _check(lib().st_plan_cache_get_stats(self.handle, ctypes.byref(out)), "st_plan_cache_get_stats")
+        return out
+
+    def destroy(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            try:
+                _lib.st_plan_cache_destroy(self.handle)
+            except Exception:      # interpreter shutdown
+                pass
+            self.handle = None
+
+    def __del__(self):
+        self.destroy()
 
 
 def st_conv_plan_info(plan: Plan) -> st_plan_info:

@@ -244,3 +244,45 @@ def test_maxpool(torch, C, dtype):
     sc.st_maxpool_nhwc(dx, dy, 2, 15, 14, C, 3, 2, 1, dtype)
     _sync(torch)
     assert np.array_equal(helpers.from_device_nhwc(dy), oracle.maxpool2d(x, 3, 2, 1))
+
+
+def test_plan_cache_dynamic_arrival(torch):
+    """The ready set changes from step to step (Section 4: the scheduler merges whichever kernels are ready).
+    Plans come from the cache; a hit is rebound to that step's buffers.  Every step's outputs are checked against
+    the oracle; two steps with the same key and different buffers are queued back to back without a host
+    synchronisation in between, and both must come out right (the rebind is ordered on the stream)."""
+    from tests import helpers
+    shapes = [ConvShape(1, 32, 14, 14, 48, 3, 3, 1, 1, "bf16", "f32"), ConvShape(2, 64, 7, 7, 64, 1, 1, 1, 0, "bf16", "f32"),
+              ConvShape(1, 16, 20, 20, 40, 3, 3, 2, 1, "bf16", "bf16"), ConvShape(1, 128, 7, 7, 128, 3, 3, 1, 1, "bf16", "f32"),
+              ConvShape(1, 24, 9, 9, 16, 5, 5, 1, 2, "f16", "f32")]
+    # two variants (inputs and output buffers) per tenant, same weights
+    var = [[helpers.Tenant(s, synth.gen_input(92, t, v, s), synth.gen_weight(92, t, 0, s)) for v in range(2)]
+           for t, s in enumerate(shapes)]
+    refs = [[v.reference() for v in tv] for tv in var]
+    cache = sc.PlanCache(4)
+    rng = np.random.default_rng(7)
+    stream = torch.cuda.Stream()
+    for step in range(14):
+        ready = [t for t in range(len(shapes)) if rng.random() < 0.6] or [int(rng.integers(len(shapes)))]
+        pick = [int(rng.integers(2)) for _ in ready]
+        tenants = [var[t][v] for t, v in zip(ready, pick)]
+        for tn in tenants:
+            tn.clear()
+        torch.cuda.synchronize()
+        plan, hit = cache.get([tn.desc() for tn in tenants], stream)
+        sc.st_conv_run(plan, stream)
+        # the same ready set again at once, on the other variant's buffers, without waiting
+        other = [var[t][1 - v] for t, v in zip(ready, pick)]
+        for tn in other:
+            tn.clear()
+        plan2, hit2 = cache.get([tn.desc() for tn in other], stream)
+        assert hit2 and plan2.handle == plan.handle
+        sc.st_conv_run(plan2, stream)
+        torch.cuda.synchronize()
+        for t, v, a, b in zip(ready, pick, tenants, other):
+            for tn, ref in ((a, refs[t][v]), (b, refs[t][1 - v])):
+                got = tn.result()
+                assert (np.abs(got - ref) <= helpers.tolerance(tn.shape, ref)).all(), f"step {step} tenant {t}"
+    st = cache.stats()
+    assert st.hits >= 14 and st.misses >= 2 and st.size <= 4
+    cache.destroy()

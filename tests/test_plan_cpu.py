@@ -274,3 +274,58 @@ def test_rebind_checks_on_host_plan():
 
 def test_status_strings():
     assert sc.lib().st_status_string(0) == b"ST_OK" and sc.lib().st_status_string(2) == b"ST_ERR_UNSUPPORTED"
+
+
+def test_plan_cache_hits_misses_eviction_and_rebinding():
+    """Host-only plan cache: the key is everything but the pointers, in tenant order; a hit rebinds the cached
+    plan to the new pointers; the least recently used plan goes first."""
+    shapes = synth.config_shapes(2)
+    cache = sc.PlanCache(2, sc.plan_opts(host_only=1))
+    a = [_desc(s) for s in shapes]
+    p1, hit = cache.get(a)
+    assert not hit and sc.st_conv_plan_info(p1).n_tenants == 4
+    # same shapes, other pointers: the same plan comes back, with the same work list
+    items1 = _as_rows(sc.st_conv_plan_worklist(p1, 0)).copy()
+    b = [_desc(s, x=0x50000 + 0x1000 * t, w=0x60000 + 0x1000 * t, y=0x70000 + 0x1000 * t) for t, s in enumerate(shapes)]
+    p2, hit = cache.get(b)
+    assert hit and p2.handle == p1.handle
+    assert np.array_equal(_as_rows(sc.st_conv_plan_worklist(p2, 0)), items1)
+    # a different ready set (subset, and another order) is a different key
+    p3, hit = cache.get(a[:3])
+    assert not hit and p3.handle != p1.handle
+    st = cache.stats()
+    assert (st.hits, st.misses, st.evictions, st.size, st.capacity) == (1, 2, 0, 2, 2)
+    p4, hit = cache.get(a[::-1])                 # cache full: evicts the 4-tenant plan (least recently used)
+    assert not hit
+    st = cache.stats()
+    assert (st.misses, st.evictions, st.size) == (3, 1, 2)
+    _, hit = cache.get(a[:3])
+    assert hit                                  # still cached
+    _, hit = cache.get(a)
+    assert not hit                              # was evicted, rebuilt
+    # an epilogue bit or a residual pointer changes the key
+    _, hit = cache.get([_desc(shapes[0])])
+    assert not hit
+    _, hit = cache.get([_desc(shapes[0], epilogue=sc.ST_EPI_RELU)])
+    assert not hit
+    # errors pass through and cache nothing
+    before = cache.stats().misses
+    with pytest.raises(sc.StError):
+        cache.get([_desc(shapes[0], y=FAKE["x"])])          # y aliases x
+    assert cache.stats().misses == before
+    with pytest.raises(sc.StError):
+        sc.PlanCache(0)
+    cache.destroy()
+
+
+def test_rebind_all_validates_and_keeps_shapes():
+    shapes = synth.config_shapes(3)
+    p = _host_plan(shapes)
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_rebind_all(p, [_desc(s) for s in shapes[:-1]])          # wrong tenant count
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_rebind_all(p, [_desc(s, y=FAKE["w"]) for s in shapes])  # y aliases w
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan_rebind_all(p, [_desc(s, x=None) for s in shapes])       # NULL x
+    sc.st_conv_plan_rebind_all(p, [_desc(s, x=0x90000) for s in shapes])
+    assert sc.st_conv_plan_info(p).n_tenants == len(shapes)
