@@ -211,6 +211,120 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                                        "conv_geomean_vs_time_only": [7.73, 7.71]}}
 
 
+def arrival_trace(steps: int = 400, p_ready: float = 0.7, capacity: int = 256, seed: int = 11):
+    """Dynamic arrival (Section 4: the scheduler merges whichever kernels are ready and caches the merged
+    kernels): a pool of 8 tenants (configs[1]'s four layers and four of configs[2]'s), a seeded Bernoulli ready
+    set per step, plans from the plan cache.  Reports the host time of the cache call (hit / miss), the hit rate,
+    and the whole trace's throughput against launching every ready tenant on its own (time-only, per-tenant
+    plans)."""
+    import numpy as np
+    import torch
+    from paper_1901_00041_amd import st_conv as sc
+    from paper_1901_00041_amd import synth
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+    shapes = synth.config_shapes(2) + synth.config_shapes(3)[:4]
+    keep, descs = [], []
+    for t, s in enumerate(shapes):
+        x = torch.randn((s.N, s.H, s.W, s.C), device="cuda").to(dt[s.dtype])
+        w = (torch.randn((s.K, s.R, s.S, s.C), device="cuda") / (s.C * s.R * s.S) ** 0.5).to(dt[s.dtype])
+        y = torch.empty((s.N, s.P, s.Q, s.K), dtype=dt[s.out_dtype], device="cuda")
+        keep.append((x, w, y))
+        descs.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype, x, w, y))
+    rng = np.random.default_rng(seed)
+    trace = []
+    for _ in range(steps):
+        ready = [t for t in range(len(shapes)) if rng.random() < p_ready] or [int(rng.integers(len(shapes)))]
+        trace.append(ready)
+    flops = sum(shapes[t].flops for ready in trace for t in ready)
+    stream = torch.cuda.Stream()
+    out = {"mode": "arrival_trace", "pool_tenants": len(shapes), "steps": steps, "p_ready": p_ready,
+           "cache_capacity": capacity, "distinct_ready_sets": len({tuple(r) for r in trace}),
+           "mean_ready": sum(len(r) for r in trace) / steps, "flops": flops}
+    # fused, through the cache: first pass cold (misses build plans), second pass warm
+    cache = sc.PlanCache(capacity)
+    for label in ("cold", "warm"):
+        t_hit, t_miss = [], []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for ready in trace:
+            h0 = time.perf_counter()
+            plan, hit = cache.get([descs[t] for t in ready], stream)
+            (t_hit if hit else t_miss).append((time.perf_counter() - h0) * 1e6)
+            sc.st_conv_run(plan, stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        out[f"fused_{label}"] = {"us_per_step": wall / steps * 1e6, "tflops": flops / wall / 1e12,
+                                 "hits": len(t_hit), "misses": len(t_miss),
+                                 "host_us_hit_median": statistics.median(t_hit) if t_hit else None,
+                                 "host_us_miss_median": statistics.median(t_miss) if t_miss else None}
+    st = cache.stats()
+    out["cache"] = {"hits": int(st.hits), "misses": int(st.misses), "evictions": int(st.evictions), "size": int(st.size)}
+    # baseline: every ready tenant on its own, per-tenant plans built once
+    solo = [sc.st_conv_plan([d], keep=keep) for d in descs]
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for ready in trace:
+            sc.st_conv_run_plans_time_only([solo[t] for t in ready], stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    out["time_only"] = {"us_per_step": wall / steps * 1e6, "tflops": flops / wall / 1e12}
+    out["speedup_vs_time_only_warm"] = out["time_only"]["us_per_step"] / out["fused_warm"]["us_per_step"]
+    cache.destroy()
+    return out
+
+
+def isolation(reps: int = 30):
+    """Predictability (Section 3 observes that identical models sharing a GPU under spatial multiplexing finish up
+    to 25% apart): R identical tenants (the Section 4.1 convolution, own weights and inputs each); per-tenant
+    completion time inside one fused launch (in-kernel clock, per work-list order) and under the space-only
+    policy (one stream per tenant, HIP events).  gap = (slowest - fastest) / slowest over the tenants' mean
+    completion times."""
+    import numpy as np
+    import torch
+    from paper_1901_00041_amd import st_conv as sc
+    out = {"mode": "isolation", "shape": "3x3 128->128 @16x16 (M=256, N=128, K=1152), bf16 in / fp32 out", "results": {}}
+    for R in (8, 32):
+        keep, descs = [], []
+        for t in range(R):
+            x = torch.randn((1, 16, 16, 128), device="cuda").to(torch.bfloat16)
+            w = (torch.randn((128, 3, 3, 128), device="cuda") / 1152 ** 0.5).to(torch.bfloat16)
+            y = torch.empty((1, 16, 16, 128), dtype=torch.float32, device="cuda")
+            keep.append((x, w, y))
+            descs.append(sc.make_desc(1, 128, 16, 16, 128, 3, 3, 1, 1, "bf16", "f32", x, w, y))
+        res = {}
+        for label, order in (("fused_longest_first", 0), ("fused_equal_progress", 2)):
+            plan = sc.st_conv_plan(descs, sc.plan_opts(order=order), keep=keep)
+            for _ in range(3):
+                sc.st_conv_run(plan)
+            torch.cuda.synchronize()
+            ends = np.stack([sc.st_conv_run_tenant_times(plan)[1] for _ in range(reps)]).astype(np.float64) / 1e3
+            mean = ends.mean(axis=0)
+            res[label] = {"completion_us_fastest": float(mean.min()), "completion_us_slowest": float(mean.max()),
+                          "gap": float((mean.max() - mean.min()) / mean.max()),
+                          "work_items": int(sc.st_conv_plan_info(plan).n_items)}
+        solo = [sc.st_conv_plan([d], keep=keep) for d in descs]
+        streams = [torch.cuda.Stream() for _ in range(R)]
+        ends = np.zeros((reps, R))
+        for rep in range(reps + 3):
+            start = torch.cuda.Event(enable_timing=True)
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(R)]
+            start.record(streams[0])
+            for t in range(R):
+                streams[t].wait_event(start)
+                sc.st_conv_run(solo[t], streams[t])
+                evs[t].record(streams[t])
+            torch.cuda.synchronize()
+            if rep >= 3:
+                ends[rep - 3] = [start.elapsed_time(e) * 1e3 for e in evs]
+        mean = ends.mean(axis=0)
+        res["space_only"] = {"completion_us_fastest": float(mean.min()), "completion_us_slowest": float(mean.max()),
+                             "gap": float((mean.max() - mean.min()) / mean.max())}
+        out["results"][f"R={R}"] = res
+    out["paper_context"] = "MPS on a V100: identical ResNet-50 models finish up to 25% apart (Section 3)"
+    return out
+
+
 def measured_traffic(cfg: int):
     """HBM bytes per fused launch from the committed counter summary (profiles/hbm_traffic.txt), or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
@@ -234,6 +348,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="run the paper's R-sweep of its three Table-1 shapes instead of the headline benchmark")
+    ap.add_argument("--arrival-trace", action="store_true",
+                    help="run a synthetic trace whose ready set of tenants changes every step, through the plan cache")
+    ap.add_argument("--isolation", action="store_true",
+                    help="per-tenant completion spread of identical tenants: fused launch vs space-only")
     ap.add_argument("--counters", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: only K fused steps of the workload and K launches of "
                          "a 64 MiB copy kernel (the known-traffic reference); prints a short JSON line")
@@ -254,6 +372,12 @@ def main():
 
     if args.paper_sweep:
         print(json.dumps(paper_sweep()))
+        return
+    if args.arrival_trace:
+        print(json.dumps(arrival_trace()))
+        return
+    if args.isolation:
+        print(json.dumps(isolation()))
         return
     if args.counters:
         run, flops, nbytes, n_launch, meta = build_workload(args.config)

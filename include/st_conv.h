@@ -69,7 +69,8 @@ typedef struct st_conv_desc {
 typedef struct st_plan_opts {
   int32_t tile_cfg;      /* 0 = choose per tenant; 1 + index into st_tile_shape() to force one       */
   int32_t split_k;       /* 0 = choose per tenant; >= 1 forces that factor (clamped to the K steps)  */
-  int32_t order;         /* 0 = longest work item first (default); 1 = tenant-major                  */
+  int32_t order;         /* 0 = longest work item first (default); 1 = tenant-major; 2 = equal        */
+                         /* progress: tenants interleaved in proportion to their item counts         */
   int32_t host_only;     /* 1 = build the tables on the host only (no device calls); run => error    */
   int32_t target_items;  /* 0 = default; else the workgroup slots the planner's cost model fills      */
   int32_t rows_per_tile; /* 0 = choose; 1, 2 or 4 forces the output rows per work item of row-tiled   */
@@ -138,6 +139,14 @@ st_status st_conv_run(const st_plan* plan, void* hip_stream);
  * at start, [5] hardware id (XCC id << 32 | HW_ID register), [6] 100 MHz wall clock at the end,
  * [7] unused. */
 st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream, uint64_t* stamps, int64_t capacity);
+
+/* Per-tenant timing of one fused launch (the per-kernel monitoring Section 4 asks of the scheduler; the
+ * predictability question of Section 3).  first_start_ns[t] and last_end_ns[t] (HOST arrays of n_tenants
+ * entries, n_tenants = the plan's) receive the time from the start of the launch's first workgroup to the
+ * start of tenant t's first workgroup and to the end of its last one, from the 100 MHz constant clock
+ * (10 ns resolution).  Synchronous diagnostic, like st_conv_run_profiled. */
+st_status st_conv_run_tenant_times(const st_plan* plan, void* hip_stream, int64_t* first_start_ns,
+                                   int64_t* last_end_ns, int32_t n_tenants);
 
 /* Time-only policy (Section 3, Figure 6): one launch per tenant on one in-order stream, no host
  * synchronisation in between.  Same kernel, same tiles, same work items as st_conv_run. */

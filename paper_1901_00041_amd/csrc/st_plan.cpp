@@ -364,7 +364,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
   std::memset(&o, 0, sizeof(o));
   if (opts) o = *opts;
   if (o.tile_cfg < 0 || o.tile_cfg > kNumTileCfgs) return fail(ST_ERR_INVALID_ARG, "opts.tile_cfg out of range");
-  if (o.split_k < 0 || o.order < 0 || o.order > 1 || o.target_items < 0 ||
+  if (o.split_k < 0 || o.order < 0 || o.order > 2 || o.target_items < 0 ||
       !(o.rows_per_tile == 0 || o.rows_per_tile == 1 || o.rows_per_tile == 2 || o.rows_per_tile == 4) ||
       o.reserved[0] != 0 || o.reserved[1] != 0)
     return fail(ST_ERR_INVALID_ARG, "opts: negative or unknown value");
@@ -455,6 +455,23 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       xcd_arrange(p->items_tenant.data() + ti.item_begin, ti.item_count, 0, ti);
     }
     if (o.order == 1) p->items_fused = p->items_tenant;
+    if (o.order == 2) {
+      // equal progress: position by position, the tenant that is furthest behind its share of the launch goes
+      // next (the one minimising (emitted + 1) / count; lowest tenant on ties), taking its items in their
+      // tenant-major order
+      std::vector<int64_t> emitted((size_t)n_tenants, 0);
+      for (size_t q = 0; q < p->items_fused.size(); ++q) {
+        int best = -1;
+        for (int t = 0; t < n_tenants; ++t) {
+          const int64_t c = p->info[t].item_count;
+          if (emitted[t] >= c) continue;
+          // (emitted[t] + 1) / c < (emitted[best] + 1) / c_best, in integers
+          if (best < 0 || (emitted[t] + 1) * p->info[best].item_count < (emitted[best] + 1) * c) best = t;
+        }
+        p->items_fused[q] = p->items_tenant[(size_t)(p->info[best].item_begin + emitted[best])];
+        ++emitted[best];
+      }
+    }
     if (o.order == 0) {
       auto cost = [&](const st_work_item& it) {
         const st_tenant_info& ti = p->info[it.tenant];
@@ -538,6 +555,33 @@ extern "C" st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream,
   if (e == hipSuccess) e = hipMemcpy(stamps, d, (size_t)n * kProfSlots * 8, hipMemcpyDeviceToHost);
   (void)hipFree(d);
   if (e != hipSuccess) return hip_fail(e, "st_conv_run_profiled");
+  return ST_OK;
+}
+
+extern "C" st_status st_conv_run_tenant_times(const st_plan* plan, void* hip_stream, int64_t* first_start_ns,
+                                              int64_t* last_end_ns, int32_t n_tenants) {
+  st_status s = check_runnable(plan);
+  if (s != ST_OK) return s;
+  if (!first_start_ns || !last_end_ns) return fail(ST_ERR_INVALID_ARG, "NULL output");
+  if (n_tenants != (int32_t)plan->tenants.size()) return fail(ST_ERR_INVALID_ARG, "n_tenants differs from the plan's");
+  const size_t n = plan->items_fused.size();
+  std::vector<uint64_t> stamps;
+  try {
+    stamps.resize(n * kProfSlots);
+  } catch (const std::bad_alloc&) {
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  s = st_conv_run_profiled(plan, hip_stream, stamps.data(), (int64_t)stamps.size());
+  if (s != ST_OK) return s;
+  uint64_t t0 = ~(uint64_t)0;
+  for (size_t i = 0; i < n; ++i) t0 = std::min(t0, stamps[i * kProfSlots + 4]);
+  for (int t = 0; t < n_tenants; ++t) { first_start_ns[t] = -1; last_end_ns[t] = -1; }
+  for (size_t i = 0; i < n; ++i) {
+    const int t = plan->items_fused[i].tenant;
+    const int64_t b = (int64_t)(stamps[i * kProfSlots + 4] - t0) * 10, e = (int64_t)(stamps[i * kProfSlots + 6] - t0) * 10;
+    if (first_start_ns[t] < 0 || b < first_start_ns[t]) first_start_ns[t] = b;
+    if (e > last_end_ns[t]) last_end_ns[t] = e;
+  }
   return ST_OK;
 }
 

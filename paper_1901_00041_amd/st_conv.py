@@ -18,7 +18,7 @@ ST_LAYOUT_NHWC_KRSC = 0
 ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
-EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_time_only", "st_conv_run_space_only",
+EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
         L.st_conv_run_time_only.argtypes = [vp, vp]
         L.st_conv_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
+        L.st_conv_run_tenant_times.argtypes = [vp, vp, P(i64), P(i64), i32]
+        L.st_conv_run_tenant_times.restype = i32
         L.st_conv_plan_rebind.argtypes = [vp, i32, vp, vp, vp, vp]
         L.st_conv_plan_rebind_all.argtypes = [vp, P(st_conv_desc), i32, vp]
         L.st_plan_cache_create.argtypes = [i32, P(st_plan_opts), P(vp)]
@@ -219,6 +221,16 @@ def st_conv_run_profiled(plan: Plan, stream=None) -> np.ndarray:
     _check(lib().st_conv_run_profiled(plan.handle, _stream(stream), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
                                       out.size), "st_conv_run_profiled")
     return out[:n]
+
+
+def st_conv_run_tenant_times(plan: Plan, stream=None):
+    """One fused launch with per-tenant timing; returns (first_start_ns, last_end_ns) int64 arrays."""
+    n = int(st_conv_plan_info(plan).n_tenants)
+    a, b = np.zeros(max(n, 1), dtype=np.int64), np.zeros(max(n, 1), dtype=np.int64)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    _check(lib().st_conv_run_tenant_times(plan.handle, _stream(stream), a.ctypes.data_as(i64p), b.ctypes.data_as(i64p), n),
+           "st_conv_run_tenant_times")
+    return a[:n], b[:n]
 
 
 def st_conv_run_time_only(plan: Plan, stream=None) -> None:

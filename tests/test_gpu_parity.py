@@ -91,6 +91,18 @@ def test_auto_plan_small(torch):
     _run_small(torch, helpers)
 
 
+def test_equal_progress_order_and_tenant_times(torch):
+    """order = 2 interleaves the tenants; results do not depend on the order of the work list.  The per-tenant
+    timing call reports, for every tenant, a start inside the launch and an end after it."""
+    from tests import helpers
+    tenants, plan = _run_small(torch, helpers, order=2)
+    first, last = sc.st_conv_run_tenant_times(plan)
+    assert len(first) == len(tenants) and (first >= 0).all() and (last > first).all()
+    assert first.min() == 0 and last.max() < 1_000_000        # the launch takes far less than a millisecond
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"small[{i}] after the timed launch")
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])
 def test_config_parity_all_policies(torch, cfg):
     """Full-size configurations 1-4, element by element, under the three issue policies; the three

@@ -119,7 +119,8 @@ def _as_rows(items):
 
 
 @pytest.mark.parametrize("cfg,opts", [(1, {}), (2, {}), (3, {}), (4, {}), (2, {"tile_cfg": 6, "split_k": 5}),
-                                      (4, {"tile_cfg": 1}), (3, {"order": 1}), (4, {"split_k": 3, "target_items": 64})])
+                                      (4, {"tile_cfg": 1}), (3, {"order": 1}), (4, {"split_k": 3, "target_items": 64}),
+                                      (4, {"order": 2}), (2, {"order": 2})])
 def test_work_lists_bit_exact(cfg, opts):
     shapes = synth.config_shapes(cfg)
     p = _host_plan(shapes, **opts)
@@ -132,6 +133,18 @@ def test_work_lists_bit_exact(cfg, opts):
     assert np.array_equal(np.unique(fused, axis=0), np.unique(want, axis=0)) and len(np.unique(fused, axis=0)) == len(want)
     if opts.get("order") == 1:
         assert np.array_equal(fused, want)
+    if opts.get("order") == 2:
+        # equal progress: the tenant furthest behind its share goes next ((emitted + 1) / count smallest, lowest
+        # tenant on ties), taking its items in tenant-major order -- restated here with exact fractions
+        from fractions import Fraction
+        counts = [int(sc.st_conv_plan_tenant_info(p, t).item_count) for t in range(len(shapes))]
+        begins = [int(sc.st_conv_plan_tenant_info(p, t).item_begin) for t in range(len(shapes))]
+        emitted = [0] * len(shapes)
+        for q in range(len(want)):
+            t = min((t for t in range(len(shapes)) if emitted[t] < counts[t]),
+                    key=lambda t: (Fraction(emitted[t] + 1, counts[t]), t))
+            assert np.array_equal(fused[q], want[begins[t] + emitted[t]]), f"position {q}"
+            emitted[t] += 1
     # K coverage: the slices of a tile tile [0, k_steps) without gap or overlap, and cover Kgemm
     for t, s in enumerate(shapes):
         ti = sc.st_conv_plan_tenant_info(p, t)
