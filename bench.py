@@ -38,8 +38,10 @@ CONFIG_TEXT = {
 }
 
 
-def build_workload(cfg: int):
-    """Returns (runner, flops, bytes, n_launches_fused, meta).  runner(policy, stream) issues one step."""
+def build_workload(cfg: int, copies: int = 1):
+    """Returns (runner, flops, bytes, n_launches_fused, meta).  runner(policy, stream) issues one step.
+    With copies > 1 (configurations 1-4) the tensors exist that many times and the "fused_cold" policy rotates
+    through them, so that a launch finds none of its operands in the caches."""
     import torch
     from paper_1901_00041_amd import st_conv as sc
     from paper_1901_00041_amd import synth
@@ -65,10 +67,21 @@ def build_workload(cfg: int):
     info = sc.st_conv_plan_info(plan)
     streams = [torch.cuda.Stream() for _ in shapes]
     solo = [sc.st_conv_plan([d], keep=keep) for d in descs]      # each tenant planned alone (retuned baselines)
+    cold_plans, turn = [], [0]
+    for _ in range(copies - 1):
+        cd = []
+        for (x, w, y), s in zip(keep[:len(shapes)], shapes):
+            x2, w2, y2 = x.clone(), w.clone(), torch.empty_like(y)
+            keep.append((x2, w2, y2))
+            cd.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype, x2, w2, y2))
+        cold_plans.append(sc.st_conv_plan(cd, keep=keep))
 
     def run(policy: str, stream):
         if policy == "fused":
             sc.st_conv_run(plan, stream)
+        elif policy == "fused_cold":
+            turn[0] = (turn[0] + 1) % (len(cold_plans) + 1)
+            sc.st_conv_run(cold_plans[turn[0] - 1] if turn[0] else plan, stream)
         elif policy == "time_only":
             sc.st_conv_run_time_only(plan, stream)
         elif policy == "space_only":
@@ -79,8 +92,8 @@ def build_workload(cfg: int):
             sc.st_conv_run_plans_space_only(solo, [stream] + streams[1:])
 
     return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan),
-                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo),
-                                                      "retuned": True}
+                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans),
+                                                      "retuned": True, "copies": copies}
 
 
 def time_policy(run, policy: str, steps: int, warmup: int):
@@ -100,6 +113,23 @@ def time_policy(run, policy: str, steps: int, warmup: int):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return wall_ms / steps, e0.elapsed_time(e1) / steps
+
+
+def launch_percentiles(run, policy: str, n: int = 300):
+    """p10 / median / p90 of single steps, each bracketed by its own pair of HIP events on the launch stream."""
+    import torch
+    stream = torch.cuda.Stream()
+    for _ in range(20):
+        run(policy, stream)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:
+        a.record(stream)
+        run(policy, stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    return {"p10_us": t[n // 10], "median_us": t[n // 2], "p90_us": t[(9 * n) // 10]}
 
 
 def launch_floor_us(n: int = 2000) -> float:
@@ -346,6 +376,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-sweep", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the cold-cache variant and the per-launch percentiles (keeps a kernel trace of the run "
+                         "to the launches of the three policies)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="run the paper's R-sweep of its three Table-1 shapes instead of the headline benchmark")
     ap.add_argument("--arrival-trace", action="store_true",
@@ -398,7 +431,10 @@ def main():
     floor_us = launch_floor_us()
 
     def measure(cfg: int, k: int, w: int):
-        run, flops, nbytes, n_launch, meta = build_workload(cfg)
+        # enough copies of the tensors to exceed the 256 MB memory-side cache several times over
+        copies = 1 if cfg == 5 else max(3, int(1.2e9 // max(1, {1: 475e3, 2: 8.52e6, 3: 14.25e6, 4: 104.4e6}[cfg])))
+        copies = 1 if args.no_extras else min(copies, 160)
+        run, flops, nbytes, n_launch, meta = build_workload(cfg, copies)
         out = {"flops": flops, "algorithmic_bytes": nbytes, "plan_build_us": round(meta["plan_build_us"], 1),
                "work_items": meta["n_items"], "fused_launches_per_step": n_launch}
         pols = ["fused", "time_only", "space_only"] + (["time_only_retuned", "space_only_retuned"] if meta.get("retuned") else [])
@@ -412,6 +448,12 @@ def main():
         out["speedup_vs_time_only"] = t_time / out["fused"]["ms_per_step"]
         out["speedup_vs_space_only"] = t_space / out["fused"]["ms_per_step"]
         out["pct_bf16_mfma_peak"] = 100.0 * out["fused"]["tflops"] / PEAK_BF16_TFLOPS
+        if not args.no_extras:
+            out["fused"].update(launch_percentiles(run, "fused", 100 if cfg == 5 else 300))
+        if meta.get("copies", 1) > 1:
+            wall_ms, ev_ms = time_policy(run, "fused_cold", k, w)
+            out["fused_cold"] = {"ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12,
+                                 "tensor_copies": meta["copies"], "rotated_bytes": meta["copies"] * nbytes}
         return out
 
     head = measure(args.config, steps, warmup)
@@ -460,7 +502,8 @@ def main():
                    "tenants": __import__("paper_1901_00041_amd.synth", fromlist=["x"]).N_TENANTS[args.config]},
         "pct_bf16_mfma_peak": head["pct_bf16_mfma_peak"],
         "speedup_vs_time_only": head["speedup_vs_time_only"], "speedup_vs_space_only": head["speedup_vs_space_only"],
-        "policies": {k: head[k] for k in ("fused", "time_only", "space_only", "time_only_retuned", "space_only_retuned") if k in head},
+        "policies": {k: head[k] for k in ("fused", "fused_cold", "time_only", "space_only", "time_only_retuned",
+                                          "space_only_retuned") if k in head},
         "launch_floor_us": floor_us, "plan_build_us": head["plan_build_us"], "work_items": head["work_items"],
         "gpu_max_hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "default(4)"),
         "roofline": roof,

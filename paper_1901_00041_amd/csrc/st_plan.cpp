@@ -128,8 +128,6 @@ struct Option {
   double item_time, area;
 };
 
-// Row tile eligibility (see conv_tile_rows): 16-bit types, S*C <= 32, image rows a multiple of 16 bytes,
-// stride*C even, LDS footprint within the allocation.
 // Bytes of one image row in the row tile's LDS array: left padding, the row, right padding, rounded up to
 // whole 16-byte vectors, plus the 64 bytes the operand read of the last pixel may run past its patch.
 static int row_tile_pitch(const st_conv_desc& d) {
@@ -138,6 +136,8 @@ static int row_tile_pitch(const st_conv_desc& d) {
   return (int)std::min<int64_t>(pitch, 1 << 24);
 }
 
+// Row tile eligibility (see conv_tile_rows): 16-bit types, 8 <= S*C <= 32, image rows a multiple of 16 bytes,
+// stride*C even, LDS footprint within the allocation.
 static bool row_tile_ok(const st_conv_desc& d) {
   if (d.in_dtype == ST_DT_F32) return false;
   if (d.C % 8 == 0) return false;                       // the vector kernels are better
