@@ -155,7 +155,8 @@ st_status st_conv_run_time_only(const st_plan* plan, void* hip_stream);
 /* Space-only policy (Section 3 "explicit spatial multiplexing", Figure 6): tenant t is launched on
  * hip_streams[t % n_streams].  hip_streams[0] is the anchor: every other stream first waits for the
  * work already queued on it, and on return it waits for every other stream, so work queued on
- * hip_streams[0] afterwards (e.g. a timing event) follows all tenants. */
+ * hip_streams[0] afterwards (e.g. a timing event) follows all tenants.  The first space-only run of a
+ * plan creates the events it forks and joins with; later runs create nothing. */
 st_status st_conv_run_space_only(const st_plan* plan, void* const* hip_streams, int32_t n_streams);
 
 /* The two baselines with one plan per tenant: every plan is issued as its own launch, serially on one

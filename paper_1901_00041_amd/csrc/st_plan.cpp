@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -50,7 +51,8 @@ struct st_plan {
   TenantDev* d_tenants = nullptr;
   st_work_item* d_items_fused = nullptr;
   st_work_item* d_items_tenant = nullptr;
-  char* d_workspace = nullptr;              // all tenants' split-K partials, then all counters
+  char* d_arena = nullptr;                  // the one device allocation the four pointers below point into
+  char* d_workspace = nullptr;              // split-K counters, then all tenants' partial tiles
   hipEvent_t ev_fork = nullptr;
   std::vector<hipEvent_t> ev_join;          // one per stream slot used by space-only
   // pinned staging slots for stream-ordered uploads of the tenant table (st_conv_plan_rebind_all)
@@ -258,7 +260,8 @@ static std::vector<Option> tenant_options(const st_conv_desc& d, int64_t M, int6
 
 // For a bound `limit` on the item time, each tenant takes its cheapest (smallest area) option that meets
 // the bound, or its fastest option if none does; returns the modelled launch duration.
-static double evaluate(const std::vector<std::vector<Option>>& opts, double limit, int slots, std::vector<int>* pick) {
+static void evaluate_parts(const std::vector<std::vector<Option>>& opts, double limit, std::vector<int>* pick,
+                           double* out_longest, double* out_area) {
   double area = 0.0, longest = 0.0;
   pick->assign(opts.size(), 0);
   for (size_t t = 0; t < opts.size(); ++t) {
@@ -273,35 +276,68 @@ static double evaluate(const std::vector<std::vector<Option>>& opts, double limi
     area += opts[t][best].area;
     longest = std::max(longest, opts[t][best].item_time);
   }
+  *out_longest = longest;
+  *out_area = area;
+}
+
+static double evaluate(const std::vector<std::vector<Option>>& opts, double limit, int slots, std::vector<int>* pick) {
+  double longest = 0.0, area = 0.0;
+  evaluate_parts(opts, limit, pick, &longest, &area);
   return std::max(longest, area / slots);
 }
 
+// Minimise the modelled duration over the candidate bounds (the item times of all options).  As the bound grows
+// every tenant's chosen item time can only grow and its area only shrink, so the duration is the maximum of a
+// non-decreasing and a non-increasing function of the bound: bisect for the crossing and compare its two sides.
+// ST_PLAN_EXHAUSTIVE=1 in the environment evaluates every candidate instead (the tests compare the two).
 static void choose_all(const std::vector<std::vector<Option>>& opts, int slots, std::vector<int>* pick) {
   std::vector<double> limits;
   for (const auto& v : opts)
     for (const Option& op : v) limits.push_back(op.item_time);
   std::sort(limits.begin(), limits.end());
   limits.erase(std::unique(limits.begin(), limits.end()), limits.end());
-  double best = -1.0;
+  if (limits.empty()) { pick->assign(opts.size(), 0); return; }
   std::vector<int> cur;
-  for (double lim : limits) {
-    const double d = evaluate(opts, lim, slots, &cur);
-    if (best < 0 || d < best) { best = d; *pick = cur; }
+  const char* ex = std::getenv("ST_PLAN_EXHAUSTIVE");
+  if (ex && ex[0] == '1') {
+    double best = -1.0;
+    for (double lim : limits) {
+      const double d = evaluate(opts, lim, slots, &cur);
+      if (best < 0 || d < best) { best = d; *pick = cur; }
+    }
+    return;
   }
-  if (best < 0) pick->assign(opts.size(), 0);
+  // first candidate whose longest item is at least its area share
+  auto longest_wins = [&](size_t i) {
+    double longest = 0.0, area = 0.0;
+    evaluate_parts(opts, limits[i], &cur, &longest, &area);
+    return longest >= area / slots;
+  };
+  size_t lo = 0, hi = limits.size();     // invariant: candidates below lo are area-bound, hi and above longest-bound
+  while (lo < hi) {
+    const size_t mid = (lo + hi) / 2;
+    if (longest_wins(mid)) hi = mid; else lo = mid + 1;
+  }
+  size_t best_i = lo < limits.size() ? lo : limits.size() - 1;
+  double best = evaluate(opts, limits[best_i], slots, pick);
+  // the area-bound side, and any equal durations further left (the smallest bound wins ties)
+  for (size_t i = best_i; i-- > 0;) {
+    const double d = evaluate(opts, limits[i], slots, &cur);
+    if (d > best) break;
+    best = d;
+    *pick = cur;
+  }
 }
 
 static void destroy_device(st_plan* p) {
-  if (p->d_tenants) (void)hipFree(p->d_tenants);
+  if (p->d_arena) (void)hipFree(p->d_arena);
+  p->d_arena = nullptr;
   for (int i = 0; i < st_plan::kStageSlots; ++i) {
     if (p->h_stage[i]) (void)hipHostFree(p->h_stage[i]);
     if (p->ev_stage[i]) (void)hipEventDestroy(p->ev_stage[i]);
     p->h_stage[i] = nullptr;
     p->ev_stage[i] = nullptr;
   }
-  if (p->d_items_fused) (void)hipFree(p->d_items_fused);
-  if (p->d_items_tenant) (void)hipFree(p->d_items_tenant);
-  if (p->d_workspace) (void)hipFree(p->d_workspace);
   if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
   for (hipEvent_t e : p->ev_join)
     if (e) (void)hipEventDestroy(e);
@@ -312,10 +348,12 @@ static void destroy_device(st_plan* p) {
   p->ev_join.clear();
 }
 
+// Device side of a plan: ONE allocation holding [tenant table][fused list][tenant-major list][split-K counters]
+// [split-K partial tiles], filled by one copy (the counters travel as zeros); the partial tiles need no
+// initialisation.  Events for the space-only fork/join are created on first use.
 static st_status upload(st_plan* p) {
   const size_t n = p->tenants.size();
   if (n == 0) return ST_OK;
-  // workspace: partial tiles of every split-K tenant, then the counters
   size_t ws_floats = 0, counters = 0;
   for (size_t t = 0; t < n; ++t) {
     const st_tenant_info& ti = p->info[t];
@@ -326,30 +364,48 @@ static st_status upload(st_plan* p) {
   }
   p->workspace_bytes = (int64_t)(ws_floats * 4 + counters * 4);
   if (p->host_only) return ST_OK;
-  if (p->workspace_bytes > 0) {
-    ST_HIP(hipMalloc((void**)&p->d_workspace, (size_t)p->workspace_bytes));
-    ST_HIP(hipMemset(p->d_workspace + ws_floats * 4, 0, counters * 4));
-    size_t wf = 0, ct = 0;
-    for (size_t t = 0; t < n; ++t) {
-      const st_tenant_info& ti = p->info[t];
-      if (ti.split_k > 1) {
-        p->tenants[t].ws = (float*)p->d_workspace + wf;
-        p->tenants[t].counters = (uint32_t*)(p->d_workspace + ws_floats * 4) + ct;
-        wf += (size_t)ti.tiles_m * ti.tiles_n * ti.split_k * ti.MT * ti.NT;
-        ct += (size_t)ti.tiles_m * ti.tiles_n;
-      }
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  const size_t ib = p->items_fused.size() * sizeof(st_work_item);
+  const size_t off_fused = up(n * sizeof(TenantDev));
+  const size_t off_tenant = off_fused + up(ib);
+  const size_t off_counters = off_tenant + up(ib);
+  const size_t off_ws = off_counters + up(counters * 4);
+  const size_t total = off_ws + ws_floats * 4;
+  ST_HIP(hipMalloc((void**)&p->d_arena, total));
+  p->d_tenants = (TenantDev*)p->d_arena;
+  p->d_items_fused = (st_work_item*)(p->d_arena + off_fused);
+  p->d_items_tenant = (st_work_item*)(p->d_arena + off_tenant);
+  p->d_workspace = p->d_arena + off_counters;
+  size_t wf = 0, ct = 0;
+  for (size_t t = 0; t < n; ++t) {
+    const st_tenant_info& ti = p->info[t];
+    if (ti.split_k > 1) {
+      p->tenants[t].ws = (float*)(p->d_arena + off_ws) + wf;
+      p->tenants[t].counters = (uint32_t*)(p->d_arena + off_counters) + ct;
+      wf += (size_t)ti.tiles_m * ti.tiles_n * ti.split_k * ti.MT * ti.NT;
+      ct += (size_t)ti.tiles_m * ti.tiles_n;
     }
   }
-  ST_HIP(hipMalloc((void**)&p->d_tenants, n * sizeof(TenantDev)));
-  ST_HIP(hipMemcpy(p->d_tenants, p->tenants.data(), n * sizeof(TenantDev), hipMemcpyHostToDevice));
-  const size_t ib = p->items_fused.size() * sizeof(st_work_item);
-  ST_HIP(hipMalloc((void**)&p->d_items_fused, ib));
-  ST_HIP(hipMalloc((void**)&p->d_items_tenant, ib));
-  ST_HIP(hipMemcpy(p->d_items_fused, p->items_fused.data(), ib, hipMemcpyHostToDevice));
-  ST_HIP(hipMemcpy(p->d_items_tenant, p->items_tenant.data(), ib, hipMemcpyHostToDevice));
+  std::vector<char> host;
+  try {
+    host.assign(off_ws, 0);
+  } catch (const std::bad_alloc&) {
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  std::memcpy(host.data(), p->tenants.data(), n * sizeof(TenantDev));
+  std::memcpy(host.data() + off_fused, p->items_fused.data(), ib);
+  std::memcpy(host.data() + off_tenant, p->items_tenant.data(), ib);
+  ST_HIP(hipMemcpy(p->d_arena, host.data(), off_ws, hipMemcpyHostToDevice));
+  return ST_OK;
+}
+
+// Fork/join events of the space-only policy, made when that policy first runs on the plan.
+static st_status ensure_events(const st_plan* cp) {
+  st_plan* p = const_cast<st_plan*>(cp);
+  if (p->ev_fork) return ST_OK;
   ST_HIP(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
-  p->ev_join.assign(n, nullptr);
-  for (size_t t = 0; t < n; ++t) ST_HIP(hipEventCreateWithFlags(&p->ev_join[t], hipEventDisableTiming));
+  p->ev_join.assign(p->tenants.size(), nullptr);
+  for (size_t t = 0; t < p->tenants.size(); ++t) ST_HIP(hipEventCreateWithFlags(&p->ev_join[t], hipEventDisableTiming));
   return ST_OK;
 }
 
@@ -473,14 +529,39 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       }
     }
     if (o.order == 0) {
-      auto cost = [&](const st_work_item& it) {
-        const st_tenant_info& ti = p->info[it.tenant];
-        const int begin = (int)it.k_split_idx * ti.k_steps_per_split;
-        const int steps = std::min(ti.k_steps, begin + ti.k_steps_per_split) - begin;
-        return (int64_t)(steps * kStepCost[ti.tile_cfg] + kEpiCost[ti.tile_cfg]);
-      };
-      std::stable_sort(p->items_fused.begin(), p->items_fused.end(),
-                       [&](const st_work_item& a, const st_work_item& b) { return cost(a) > cost(b); });
+      // All items of a tenant cost the same except those of a shorter last K slice, so sorting the items by cost
+      // (stably, from the nested tenant-major order) is sorting at most two runs per tenant.
+      struct Run { int tenant; int which; int64_t cost; };     // which: -1 all items, 0 full slices, 1 the last slice
+      std::vector<Run> runs;
+      runs.reserve((size_t)n_tenants * 2);
+      for (int t = 0; t < n_tenants; ++t) {
+        const st_tenant_info& ti = p->info[t];
+        const int last_steps = ti.k_steps - (ti.split_k - 1) * ti.k_steps_per_split;
+        auto cost = [&](int steps) { return (int64_t)(steps * kStepCost[ti.tile_cfg] + kEpiCost[ti.tile_cfg]); };
+        if (ti.split_k == 1 || last_steps == ti.k_steps_per_split) {
+          runs.push_back({t, -1, cost(ti.split_k == 1 ? ti.k_steps : ti.k_steps_per_split)});
+        } else {
+          runs.push_back({t, 0, cost(ti.k_steps_per_split)});
+          runs.push_back({t, 1, cost(last_steps)});
+        }
+      }
+      std::stable_sort(runs.begin(), runs.end(), [](const Run& a, const Run& b) { return a.cost > b.cost; });
+      p->items_fused.clear();
+      for (const Run& r : runs) {
+        const st_tenant_info& ti = p->info[r.tenant];
+        for (int tm = 0; tm < ti.tiles_m; ++tm)
+          for (int tn = 0; tn < ti.tiles_n; ++tn)
+            for (int s = 0; s < ti.split_k; ++s) {
+              if (r.which >= 0 && (s == ti.split_k - 1) != (r.which == 1)) continue;
+              st_work_item it;
+              it.tenant = (uint16_t)r.tenant;
+              it.k_split_idx = (uint16_t)s;
+              it.tile_m = (uint32_t)tm;
+              it.tile_n = (uint32_t)tn;
+              it.reserved = 0;
+              p->items_fused.push_back(it);
+            }
+      }
       // within every run of one tenant's items, place the items that read the same operand slice on one XCD
       for (size_t b = 0; b < p->items_fused.size();) {
         size_t e = b + 1;
@@ -604,6 +685,8 @@ extern "C" st_status st_conv_run_space_only(const st_plan* plan, void* const* hi
   hipStream_t anchor = (hipStream_t)hip_streams[0];
   const size_t used = std::min<size_t>(n, (size_t)n_streams);
   if (used > 1) {
+    s = ensure_events(plan);
+    if (s != ST_OK) return s;
     ST_HIP(hipEventRecord(plan->ev_fork, anchor));
     for (size_t i = 1; i < used; ++i) ST_HIP(hipStreamWaitEvent((hipStream_t)hip_streams[i], plan->ev_fork, 0));
   }
@@ -644,8 +727,10 @@ extern "C" st_status st_conv_run_plans_space_only(const st_plan* const* plans, i
   // fork: plans[0]'s event marks the work already queued on the anchor stream
   const st_plan* first = nullptr;
   for (int32_t i = 0; i < n_plans && !first; ++i)
-    if (plans[i]->ev_fork) first = plans[i];
+    if (!plans[i]->tenants.empty()) first = plans[i];
   if (used > 1 && first) {
+    st_status s = ensure_events(first);
+    if (s != ST_OK) return s;
     ST_HIP(hipEventRecord(first->ev_fork, anchor));
     for (int32_t i = 1; i < used; ++i) ST_HIP(hipStreamWaitEvent((hipStream_t)hip_streams[i], first->ev_fork, 0));
   }
@@ -657,8 +742,10 @@ extern "C" st_status st_conv_run_plans_space_only(const st_plan* const* plans, i
   for (int32_t sidx = 1; sidx < used; ++sidx) {
     const st_plan* last = nullptr;
     for (int32_t i = sidx; i < n_plans; i += n_streams)
-      if (!plans[i]->ev_join.empty()) last = plans[i];
+      if (!plans[i]->tenants.empty()) last = plans[i];
     if (!last) continue;
+    st_status s = ensure_events(last);
+    if (s != ST_OK) return s;
     ST_HIP(hipEventRecord(last->ev_join[0], (hipStream_t)hip_streams[sidx]));
     ST_HIP(hipStreamWaitEvent(anchor, last->ev_join[0], 0));
   }

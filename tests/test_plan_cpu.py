@@ -342,3 +342,31 @@ def test_rebind_all_validates_and_keeps_shapes():
         sc.st_conv_plan_rebind_all(p, [_desc(s, x=None) for s in shapes])       # NULL x
     sc.st_conv_plan_rebind_all(p, [_desc(s, x=0x90000) for s in shapes])
     assert sc.st_conv_plan_info(p).n_tenants == len(shapes)
+
+
+def test_planner_bisection_matches_exhaustive_search():
+    """The planner bisects over the candidate bounds; with ST_PLAN_EXHAUSTIVE=1 it evaluates every bound.  Both
+    must choose the same tile, split and rows per tile for every tenant, on the five configurations and on
+    random mixes of their layers."""
+    rng = np.random.default_rng(5)
+    pool = [s for cfg in (1, 2, 3, 4) for s in synth.config_shapes(cfg)] + [st.shape for st in synth.resnet50_steps()]
+    cases = [synth.config_shapes(cfg) for cfg in (1, 2, 3, 4)]
+    cases += [[pool[i] for i in rng.integers(len(pool), size=int(rng.integers(1, 20)))] for _ in range(40)]
+
+    def summary(p, n):
+        out = []
+        for t in range(n):
+            ti = sc.st_conv_plan_tenant_info(p, t)
+            out.append((ti.tile_cfg, ti.split_k, ti.rows_per_tile, ti.item_count))
+        return out
+
+    for shapes in cases:
+        for slots in (0, 64):
+            os.environ.pop("ST_PLAN_EXHAUSTIVE", None)
+            fast = summary(_host_plan(shapes, target_items=slots), len(shapes))
+            os.environ["ST_PLAN_EXHAUSTIVE"] = "1"
+            try:
+                slow = summary(_host_plan(shapes, target_items=slots), len(shapes))
+            finally:
+                os.environ.pop("ST_PLAN_EXHAUSTIVE", None)
+            assert fast == slow
