@@ -61,6 +61,7 @@ struct TenantDev {
   uint32_t y_bytes;           // size of y (and of the residual) in bytes
   int32_t rows_per_tile;      // row tile only: output rows per work item
   int32_t row_pitch;          // row tile only: bytes of one image row in LDS (padding included, multiple of 16)
+  int32_t k_across_waves;     // 1: each wavefront computes the whole tile over a quarter of every K step
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 

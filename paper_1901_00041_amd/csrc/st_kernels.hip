@@ -404,7 +404,12 @@ _Pragma("unroll")
 // double buffer.  All global loads are buffer loads whose out-of-range lanes return zero, so padding,
 // ragged tiles and the end of the K range cost no branches.  GENERIC selects element-wise gathers for
 // tensors whose channel count is not a multiple of the 16-byte vector width (e.g. C = 3).
-template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC>
+// KW ("K across wavefronts"): instead of dividing the tile's pixels and filters among the four wavefronts (each
+// operand row is then read from LDS by WCH resp. WPX of them), every wavefront computes the WHOLE tile over one
+// quarter of each K step (sub-step = wavefront index), so every staged byte is read from LDS exactly once.  After
+// the K loop the four partial tiles are summed through LDS, in wavefront order, into the accumulators the
+// pixel/filter division would have produced, and everything downstream (split-K, epilogue) is unchanged.
+template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false>
 __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int ES = ElemOf<DT>::ES;
   constexpr int VEC = 16 / ES;          // elements per 16-byte vector
@@ -422,6 +427,8 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   typedef typename MMA::Acc Acc;
   static_assert(WPX * WCH == 4 && WM % MF == 0 && WN % MF == 0, "bad tile shape");
   static_assert(2 * (MT + NT) * ROWB <= kSmemBytes, "tile does not fit the LDS allocation");
+  constexpr int TBM = MT / MF, TBN = NT / MF;       // MFMA blocks of the whole tile
+  static_assert(!KW || (NSUB == 4 && 4 * TBM * TBN * (MF * MF / 64) * 4 * 64 <= kSmemBytes), "KW needs four sub-steps per K step and room for four partial tiles");
 
   char* sA = smem;                          // [2][MT][ROWB]  patches
   char* sB = smem + 2 * MT * ROWB;          // [2][NT][ROWB]  filters
@@ -573,8 +580,32 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
     for (int j = 0; j < BN; ++j)
 #pragma unroll
       for (int v = 0; v < (int)(sizeof(Acc) / 4); ++v) acc[i][j][v] = 0.f;
+  // KW: this wavefront's partial sums of the whole tile
+  Acc part[KW ? TBM : 1][KW ? TBN : 1];
+  if constexpr (KW) {
+#pragma unroll
+    for (int i = 0; i < TBM; ++i)
+#pragma unroll
+      for (int j = 0; j < TBN; ++j)
+#pragma unroll
+        for (int v = 0; v < (int)(sizeof(Acc) / 4); ++v) part[i][j][v] = 0.f;
+  }
 
   auto compute = [&](int buf) {
+    if constexpr (KW) {
+      const char* pa = sA + (buf * MT + lrow) * ROWB + lk * 16 + wave * SUBB;
+      const char* pb = sB + (buf * NT + lrow) * ROWB + lk * 16 + wave * SUBB;
+      u32x4 wf[TBN], xf[TBM];
+#pragma unroll
+      for (int j = 0; j < TBN; ++j) wf[j] = *(const u32x4*)(pb + j * MF * ROWB);
+#pragma unroll
+      for (int i = 0; i < TBM; ++i) xf[i] = *(const u32x4*)(pa + i * MF * ROWB);
+#pragma unroll
+      for (int i = 0; i < TBM; ++i)
+#pragma unroll
+        for (int j = 0; j < TBN; ++j) part[i][j] = MMA::run(wf[j], xf[i], part[i][j]);
+      return;
+    }
     const char* pa = sA + (buf * MT + wm0 + lrow) * ROWB + lk * 16;
     const char* pb = sB + (buf * NT + wn0 + lrow) * ROWB + lk * 16;
 #pragma unroll
@@ -614,6 +645,37 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
     // remainder (fewer than D steps), nested so that each step is reached only through the previous one
     const int rem = nsteps - k;
     static_nest<D - 1>(rem, step);
+  }
+
+  if constexpr (KW) {
+    // sum the four wavefronts' partial tiles: each writes all its blocks ([wavefront][block][lane], 16-byte
+    // groups), then takes the blocks of its own share of the tile and adds the four copies in wavefront order
+    constexpr int VPB = (int)(sizeof(Acc) / 16);           // 16-byte groups per block per lane
+    f32x4* red = (f32x4*)smem;
+#pragma unroll
+    for (int i = 0; i < TBM; ++i)
+#pragma unroll
+      for (int j = 0; j < TBN; ++j)
+#pragma unroll
+        for (int g = 0; g < VPB; ++g)
+          red[((wave * TBM * TBN + i * TBN + j) * VPB + g) * 64 + lane] =
+              f32x4{part[i][j][4 * g], part[i][j][4 * g + 1], part[i][j][4 * g + 2], part[i][j][4 * g + 3]};
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < BM; ++i)
+#pragma unroll
+      for (int j = 0; j < BN; ++j) {
+        const int bi = wm0 / MF + i, bj = wn0 / MF + j;
+#pragma unroll
+        for (int g = 0; g < VPB; ++g) {
+          f32x4 sum = red[((0 * TBM * TBN + bi * TBN + bj) * VPB + g) * 64 + lane];
+#pragma unroll
+          for (int w = 1; w < 4; ++w) sum += red[((w * TBM * TBN + bi * TBN + bj) * VPB + g) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = sum[e];
+        }
+      }
+    __syncthreads();      // the partial tiles are consumed before the epilogue reuses the buffer
   }
 
   if (prof && tid == 0) prof[2] = __builtin_readcyclecounter();
@@ -914,10 +976,10 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   }
 }
 
-template <int CFG, int DT, bool GENERIC>
+template <int CFG, int DT, bool GENERIC, bool KW = false>
 __device__ __forceinline__ void run_cfg(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr TileShape s = kTileShapes[CFG];
-  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC>(T, it, smem, prof);
+  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW>(T, it, smem, prof);
 }
 
 template <int DT>
@@ -928,8 +990,16 @@ __device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item
       case 1: run_cfg<1, DT, false>(T, it, smem, prof); break;
       case 2: run_cfg<2, DT, false>(T, it, smem, prof); break;
       case 3: run_cfg<3, DT, false>(T, it, smem, prof); break;
-      case 4: run_cfg<4, DT, false>(T, it, smem, prof); break;
-      default: run_cfg<5, DT, false>(T, it, smem, prof); break;
+      // the two smallest tiles split each K step across the wavefronts (see KW above) when the planner found
+      // the K loop long enough to repay the final sum of the four partial tiles
+      case 4:
+        if (T.k_across_waves) run_cfg<4, DT, false, true>(T, it, smem, prof);
+        else run_cfg<4, DT, false>(T, it, smem, prof);
+        break;
+      default:
+        if (T.k_across_waves) run_cfg<5, DT, false, true>(T, it, smem, prof);
+        else run_cfg<5, DT, false>(T, it, smem, prof);
+        break;
     }
   } else {
     // few-channel layers: the row tile when the planner found it eligible, else element-wise gathers

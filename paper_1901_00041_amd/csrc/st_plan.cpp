@@ -122,6 +122,7 @@ static const double kGenericFirstCost = 19000.0;
 static const double kSplitCost = 5000.0, kSplitPerElem = 1.0, kSplitRoundCost = 2700.0;   // hand-off grows with the tile
 static const int kSlots = 400;                  // two workgroups resident per compute unit (512), derated because
                                                 // co-resident workgroups share one LDS pipe
+static const int kKAcrossWavesMinSteps = 6;     // shortest K loop for which the 32x64 and 16x64 tiles split K across wavefronts
 static const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
 
 struct Option {
@@ -586,6 +587,8 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0) ? 1 : 0;
       magic_for(d.C, &T.magic_c, &T.shift_c);
       magic_for(d.S, &T.magic_s, &T.shift_s);
+      // the sum of the four partial tiles costs about as much as the LDS reads saved over a few K steps
+      T.k_across_waves = (T.vec_ok && (ti.tile_cfg == 4 || ti.tile_cfg == 5) && ti.k_steps_per_split >= kKAcrossWavesMinSteps) ? 1 : 0;
       T.row_pitch = row_tile_pitch(d);
       magic_for(T.row_pitch / 16, &T.magic_nvp, &T.shift_nvp);
       magic_for(d.R, &T.magic_r, &T.shift_r);

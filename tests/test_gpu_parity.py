@@ -36,6 +36,8 @@ SMALL = [
     ConvShape(2, 3, 20, 32, 40, 7, 7, 2, 3, "bf16", "f32"),     # row tile (few channels), ragged filters
     ConvShape(1, 3, 9, 272, 72, 7, 7, 2, 3, "bf16", "bf16"),    # row tile, two pixel tiles per output row
     ConvShape(1, 4, 9, 16, 24, 3, 7, 1, 3, "f16", "f32"),       # row tile, stride 1, C = 4
+    ConvShape(1, 96, 9, 9, 40, 3, 3, 1, 1, "bf16", "f32"),      # K = 864: seven 256-byte steps, so the two smallest
+    ConvShape(1, 48, 6, 6, 24, 3, 3, 1, 1, "f32", "f32"),       #   tiles split K across wavefronts (bf16 and fp32)
 ]
 
 
