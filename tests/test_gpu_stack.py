@@ -80,3 +80,44 @@ def test_stack_policies_agree_bitwise():
         outs[policy] = stack.buf[last.dst].clone()
     assert torch.equal(outs["fused"], outs["time_only"]) and torch.equal(outs["fused"], outs["space_only"])
     assert not torch.equal(outs["fused"][0], outs["fused"][1])     # tenants differ
+
+
+def test_resnet50_stack_full_size_sampled():
+    """The configuration bench.py times: 8 tenants, co-scheduled groups, seeded weights.  For every step and two
+    tenants (rotating), 96 output points drawn with a fixed seed are recomputed one by one by the oracle from the
+    exact tensors the step read, plus residual and ReLU, and compared with the bf16 output."""
+    import torch
+    from oracle import oracle
+    from paper_1901_00041_amd.stack import ResNetStack
+    n_tenants = 8
+    stack = ResNetStack(n_tenants=n_tenants)
+    assert stack.n_launches == 49 and stack.flops == n_tenants * 8174272512
+    rng = np.random.default_rng(2024)
+    worst = 0.0
+    for gi, group in enumerate(stack.groups):
+        picks = {}
+        for i in group:
+            st = stack.steps[i]
+            s = st.shape
+            for t in ((i % n_tenants), ((i * 3 + 5) % n_tenants)):
+                idx = np.stack([rng.integers(s.N, size=96), rng.integers(s.K, size=96), rng.integers(s.P, size=96),
+                                rng.integers(s.Q, size=96)], axis=1).astype(np.int32)
+                x = _nchw(stack.view(st.src, t, s.N, s.H, s.W, s.C))
+                r = _nchw(stack.view(st.res, t, s.N, s.P, s.Q, s.K)) if st.res is not None else None
+                picks[(i, t)] = (idx, x, r)
+        stack.run_group(gi)
+        torch.cuda.synchronize()
+        for (i, t), (idx, x, r) in picks.items():
+            st = stack.steps[i]
+            s = st.shape
+            ref = oracle.conv2d_points(x, synth.gen_weight(5, t, st.index, s, 2.0), idx, s.stride, s.pad)
+            if r is not None:
+                ref = ref + r[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+            if st.relu:
+                ref = np.maximum(ref, 0.0)
+            got = _nchw(stack.view(st.dst, t, s.N, s.P, s.Q, s.K))[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+            err = np.abs(got - ref)
+            assert np.isfinite(got).all() and (err <= 1e-2 * (np.abs(ref) + 1.0)).all(), \
+                f"step {i} {st.name} tenant {t}: max err {err.max():.3e}"
+            worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
+    print(f"full-size stack, sampled: worst relative error {worst:.3e}")
