@@ -168,6 +168,13 @@ st_status st_conv_run_plans_time_only(const st_plan* const* plans, int32_t n_pla
 st_status st_conv_run_plans_space_only(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
                                        int32_t n_streams);
 
+/* plans[i] as one fused launch on hip_streams[i % n_streams], with no ordering between the streams: the
+ * free-running form of spatial multiplexing, where each tenant's stream carries its launches back to back and
+ * the caller forks and joins the streams when it needs to (once per chain of layers, say, instead of once per
+ * layer as st_conv_run_plans_space_only does). */
+st_status st_conv_run_plans_on_streams(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
+                                       int32_t n_streams);
+
 /* Replace tenant pointers (the cached-plan path of Section 4: same shapes, new inputs).  NULL keeps
  * the current pointer.  Synchronous small upload on the default stream; not for use while a run of
  * this plan is in flight. */

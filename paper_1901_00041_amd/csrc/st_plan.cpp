@@ -755,6 +755,17 @@ extern "C" st_status st_conv_run_plans_space_only(const st_plan* const* plans, i
   return ST_OK;
 }
 
+extern "C" st_status st_conv_run_plans_on_streams(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
+                                                  int32_t n_streams) {
+  if (n_plans < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or n_plans negative");
+  if (!hip_streams || n_streams <= 0) return fail(ST_ERR_INVALID_ARG, "need at least one stream");
+  for (int32_t i = 0; i < n_plans; ++i) {
+    st_status s = st_conv_run(plans[i], hip_streams[i % n_streams]);
+    if (s != ST_OK) return s;
+  }
+  return ST_OK;
+}
+
 extern "C" st_status st_conv_plan_rebind(st_plan* plan, int32_t tenant, const void* x, const void* w, void* y,
                                          const void* residual) {
   if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");

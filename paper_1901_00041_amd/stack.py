@@ -94,6 +94,9 @@ class ResNetStack:
                 self.group_plans.append(sc.st_conv_plan([d for i in g for d in step_descs[i]], plan_opts))
         self.n_items = sum(int(sc.st_conv_plan_info(p).n_items) for p in self.group_plans)
         self.n_launches = len(self.groups)
+        self._step_descs = step_descs
+        self._plan_opts = plan_opts
+        self._solo = None          # [step][tenant] plans of one tenant each, built on first use
         self._streams = [torch.cuda.Stream() for _ in range(n_tenants)]
 
     def _independent(self, group: List[int], st) -> bool:
@@ -119,24 +122,61 @@ class ResNetStack:
                 sc.st_maxpool_nhwc(self.buf[st.dst], self.buf[st.pool_dst], self.n_tenants * s.N, s.P, s.Q, s.K, 3, 2, 1,
                                    "bf16", stream)
 
+    def solo_plans(self, i: int):
+        """Step i's tenants planned one by one: the baselines' tiles when every launch has the GPU to itself."""
+        if self._solo is None:
+            self._solo = [[sc.st_conv_plan([d], self._plan_opts) for d in descs] for descs in self._step_descs]
+        return self._solo[i]
+
     def run_step(self, i: int, policy: str = "fused", stream=None) -> None:
         st = self.steps[i]
         if policy == "fused":
             sc.st_conv_run(self.plans[i], stream)
         elif policy == "time_only":
             sc.st_conv_run_time_only(self.plans[i], stream)
-        else:
+        elif policy == "space_only":
             sc.st_conv_run_space_only(self.plans[i], [stream] + self._streams[1:])
+        elif policy == "time_only_retuned":
+            sc.st_conv_run_plans_time_only(self.solo_plans(i), stream)
+        elif policy == "space_only_retuned":
+            sc.st_conv_run_plans_space_only(self.solo_plans(i), [stream] + self._streams[1:])
+        else:
+            raise ValueError(f"unknown policy {policy!r}")
         if st.pool_after:
             s = st.shape
             # all tenants' stem outputs are one contiguous batch: a single pooling launch
             sc.st_maxpool_nhwc(self.buf[st.dst], self.buf[st.pool_dst], self.n_tenants * s.N, s.P, s.Q, s.K, 3, 2, 1,
                                "bf16", stream)
 
+    def run_chains(self, stream=None) -> None:
+        """Space-only without per-layer joins: every tenant's whole chain of per-tenant launches goes to the tenant's
+        own stream; the streams fork from `stream` at the start and join it at the end."""
+        torch = self.torch
+        anchor = stream if stream is not None else torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(anchor)
+        streams = [anchor] + self._streams[1:]
+        for s in streams[1:]:
+            s.wait_event(start)
+        for i, st in enumerate(self.steps):
+            sc.st_conv_run_plans_on_streams(self.solo_plans(i), streams)      # tenant t on stream t
+            if st.pool_after:
+                s = st.shape
+                for t in range(self.n_tenants):
+                    sc.st_maxpool_nhwc(self.buf[st.dst][t], self.buf[st.pool_dst][t], s.N, s.P, s.Q, s.K, 3, 2, 1, "bf16",
+                                       streams[t])
+        for s in streams[1:]:
+            done = torch.cuda.Event()
+            done.record(s)
+            anchor.wait_event(done)
+
     def run(self, policy: str = "fused", stream=None) -> None:
         if policy == "fused":
             for gi in range(len(self.groups)):
                 self.run_group(gi, stream)
+            return
+        if policy == "space_only_chains":
+            self.run_chains(stream)
             return
         for i in range(len(self.steps)):
             self.run_step(i, policy, stream)
