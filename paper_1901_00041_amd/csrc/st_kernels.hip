@@ -146,6 +146,9 @@ __device__ __forceinline__ int fast_div(int n, uint32_t m, int L) {
 constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every buffer: the load returns 0
 
 // ---- epilogue shared by all tile kernels: (+ residual) -> ReLU -> cast -> store ---------------------
+// The transposed output rows are stored write-through (sc1), so they leave the L2 while the kernel still runs
+// instead of waiting in it for the write-back at the end of the kernel, which the next launch on the stream
+// would have to sit through.
 // acc[i][j] is the MF x MF block at pixels wm0 + i*MF, filters wn0 + j*MF of the tile whose first pixel is
 // im2col row m0 and first filter n0; rows at or past m_end are not stored.
 // The transposition buffer `smem` holds MT/PASSES pixel rows; with PASSES > 1 the tile is written out in
@@ -200,7 +203,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
       const bool ok = (MT * NV % kThreads == 0 || v < MT * NV) & (m < m_end) & (ch < Kf);
       const uint32_t off = ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset;
       const u32x4 d = *(const u32x4*)(smem + (row < MT ? row : 0) * PITCHB + cv * 16);
-      __builtin_amdgcn_raw_buffer_store_b128(d, ry, (int)off, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(d, ry, (int)off, 0, kAuxDeviceCoherent);
     }
   } else if ((Kf & 7) == 0) {
     // Transpose through LDS: accumulators go to an fp32 [pixel][filter] tile, then every lane handles 16
@@ -283,7 +286,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
 #pragma unroll
             for (int e = 0; e < 4; ++e) a[u][e] = a[u][e] > 0.f ? a[u][e] : 0.f;
           }
-          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a[u]), ry, (int)off[u], 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a[u]), ry, (int)off[u], 0, kAuxDeviceCoherent);
         }
       }
     } else {
@@ -335,7 +338,7 @@ __device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM]
             pk[2 + e] = isbf ? ((uint32_t)f32_to_bf16_rne(hi[u][2 * e]) | ((uint32_t)f32_to_bf16_rne(hi[u][2 * e + 1]) << 16))
                              : ((uint32_t)f32_to_f16_bits(hi[u][2 * e]) | ((uint32_t)f32_to_f16_bits(hi[u][2 * e + 1]) << 16));
           }
-          __builtin_amdgcn_raw_buffer_store_b128(pk, ry, (int)off[u], 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(pk, ry, (int)off[u], 0, kAuxDeviceCoherent);
         }
       }
     }
