@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16/fp16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 matrix
 PEAK_HBM_GBS = 8000.0
+PIPELINED_SLOTS = 256         # workgroup slots the planner fills per launch when two launches share the GPU
 PAPER_CONTEXT = {"space_time_over_space_only_geomean": 3.23, "space_time_over_time_only_geomean": [7.73, 7.71],
                  "hardware": "NVIDIA V100 (AWS p3), fp32 SGEMM M=256 N=128 K=1152, 2<=R<=120",
                  "note": "other hardware and precision; context only"}
@@ -61,9 +62,11 @@ def build_workload(cfg: int, copies: int = 1):
             # two independent batches in flight: passes alternate between two stacks (own activations, own weights)
             # on two streams
             if not twin:
-                twin.append(ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5, seeded_weights=False))
+                for _ in range(2):      # planned for the half of the GPU a launch gets when two are in flight
+                    twin.append(ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5, seeded_weights=False,
+                                            plan_opts=sc.plan_opts(target_items=PIPELINED_SLOTS)))
             flip[0] ^= 1
-            (twin[0] if flip[0] else stack).run("fused", pipe[flip[0]])
+            twin[flip[0]].run("fused", pipe[flip[0]])
 
         return run5, stack.flops, stack.bytes, stack.n_launches, {"plan_build_us": stack.plan_build_us, "pipelined": True,
                                                                        "n_items": stack.n_items, "keep": stack,
@@ -85,7 +88,7 @@ def build_workload(cfg: int, copies: int = 1):
     info = sc.st_conv_plan_info(plan)
     streams = [torch.cuda.Stream() for _ in shapes]
     solo = [sc.st_conv_plan([d], keep=keep) for d in descs]      # each tenant planned alone (retuned baselines)
-    cold_plans, turn, flip = [], [0], [0]
+    cold_plans, pipe_plans, turn, flip = [], [], [0], [0]
     pipe = [torch.cuda.Stream(), torch.cuda.Stream()]
     for _ in range(copies - 1):
         cd = []
@@ -94,6 +97,10 @@ def build_workload(cfg: int, copies: int = 1):
             keep.append((x2, w2, y2))
             cd.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype, x2, w2, y2))
         cold_plans.append(sc.st_conv_plan(cd, keep=keep))
+        if not pipe_plans:
+            # the pipelined form keeps two launches in flight: each is planned for half of the GPU
+            half = sc.plan_opts(target_items=PIPELINED_SLOTS)
+            pipe_plans.extend([sc.st_conv_plan(descs, half, keep=keep), sc.st_conv_plan(cd, half, keep=keep)])
 
     def run(policy: str, stream):
         if policy == "fused":
@@ -101,7 +108,7 @@ def build_workload(cfg: int, copies: int = 1):
         elif policy == "fused_pipelined":
             # two independent batches in flight: launches alternate between two sets of tensors on two streams
             flip[0] ^= 1
-            sc.st_conv_run(cold_plans[0] if flip[0] else plan, pipe[flip[0]])
+            sc.st_conv_run(pipe_plans[flip[0]], pipe[flip[0]])
         elif policy == "fused_cold":
             turn[0] = (turn[0] + 1) % (len(cold_plans) + 1)
             sc.st_conv_run(cold_plans[turn[0] - 1] if turn[0] else plan, stream)
@@ -115,7 +122,7 @@ def build_workload(cfg: int, copies: int = 1):
             sc.st_conv_run_plans_space_only(solo, [stream] + streams[1:])
 
     return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan),
-                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans),
+                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans, pipe_plans),
                                                       "retuned": True, "copies": copies, "pipelined": copies > 1}
 
 
@@ -519,7 +526,7 @@ def main():
                         "tflops": flops / (wall_ms * 1e-3) / 1e12}
         if cfg != 5:
             # free-running streams: per-tenant plans, no joins between steps (the strongest form of space-only)
-            plan, keep, streams, solo, cold_plans = meta["keep"]
+            plan, keep, streams, solo, cold_plans, _pipe_plans = meta["keep"]
             wall_ms, ev_ms = time_free_running(solo, streams, k, w)
             out["space_only_free"] = {"ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12}
             pols = pols + ["space_only_free"]
