@@ -30,7 +30,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16/fp16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 matrix
 PEAK_HBM_GBS = 8000.0
-PIPELINED_SLOTS = 256         # workgroup slots the planner fills per launch when two launches share the GPU
+# forms of the fused policy with several independent batches in flight: (streams, workgroup slots the planner fills
+# per launch when that many launches share the GPU)
+PIPELINED = {"fused_pipelined": (2, 256), "fused_pipelined4": (4, 128)}
 PAPER_CONTEXT = {"space_time_over_space_only_geomean": 3.23, "space_time_over_time_only_geomean": [7.73, 7.71],
                  "hardware": "NVIDIA V100 (AWS p3), fp32 SGEMM M=256 N=128 K=1152, 2<=R<=120",
                  "note": "other hardware and precision; context only"}
@@ -54,21 +56,28 @@ def build_workload(cfg: int, copies: int = 1):
     if cfg == 5:
         from paper_1901_00041_amd.stack import ResNetStack
         stack = ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5)
-        twin, pipe, flip = [], [torch.cuda.Stream(), torch.cuda.Stream()], [0]
+        twins, pipes, turn5 = {}, {}, {}
 
         def run5(policy: str, stream):
-            if policy != "fused_pipelined":
+            if policy not in PIPELINED:
                 return stack.run(policy, stream)
-            # two independent batches in flight: passes alternate between two stacks (own activations, own weights)
-            # on two streams
-            if not twin:
-                for _ in range(2):      # planned for the half of the GPU a launch gets when two are in flight
-                    twin.append(ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5, seeded_weights=False,
-                                            plan_opts=sc.plan_opts(target_items=PIPELINED_SLOTS)))
-            flip[0] ^= 1
-            twin[flip[0]].run("fused", pipe[flip[0]])
+            # several independent batches in flight: passes rotate over as many stacks (own activations, own weights),
+            # each on its own stream and planned for its share of the GPU
+            depth, slots = PIPELINED[policy]
+            if policy not in twins:
+                twins[policy] = [ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5, seeded_weights=False,
+                                             plan_opts=sc.plan_opts(target_items=slots)) for _ in range(depth)]
+                pipes[policy] = [torch.cuda.Stream() for _ in range(depth)]
+                turn5[policy] = 0
+            i = turn5[policy] = (turn5[policy] + 1) % depth
+            twins[policy][i].run("fused", pipes[policy][i])
 
-        return run5, stack.flops, stack.bytes, stack.n_launches, {"plan_build_us": stack.plan_build_us, "pipelined": True,
+        def new_streams5(policy):
+            if policy in pipes:
+                pipes[policy] = [torch.cuda.Stream() for _ in pipes[policy]]
+
+        return run5, stack.flops, stack.bytes, stack.n_launches, {"plan_build_us": stack.plan_build_us, "pipelined": sorted(PIPELINED),
+                                                                       "new_streams": new_streams5,
                                                                        "n_items": stack.n_items, "keep": stack,
                                                                        "retuned": True, "chains": True}
     dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
@@ -88,8 +97,7 @@ def build_workload(cfg: int, copies: int = 1):
     info = sc.st_conv_plan_info(plan)
     streams = [torch.cuda.Stream() for _ in shapes]
     solo = [sc.st_conv_plan([d], keep=keep) for d in descs]      # each tenant planned alone (retuned baselines)
-    cold_plans, pipe_plans, turn, flip = [], [], [0], [0]
-    pipe = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cold_plans, cold_descs, pipe_plans, pipe_streams, pipe_turn, turn = [], [descs], {}, {}, {}, [0]
     for _ in range(copies - 1):
         cd = []
         for (x, w, y), s in zip(keep[:len(shapes)], shapes):
@@ -97,18 +105,21 @@ def build_workload(cfg: int, copies: int = 1):
             keep.append((x2, w2, y2))
             cd.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.dtype, s.out_dtype, x2, w2, y2))
         cold_plans.append(sc.st_conv_plan(cd, keep=keep))
-        if not pipe_plans:
-            # the pipelined form keeps two launches in flight: each is planned for half of the GPU
-            half = sc.plan_opts(target_items=PIPELINED_SLOTS)
-            pipe_plans.extend([sc.st_conv_plan(descs, half, keep=keep), sc.st_conv_plan(cd, half, keep=keep)])
+        cold_descs.append(cd)
+    for name, (depth, slots) in PIPELINED.items():
+        if copies >= depth:
+            # that many launches in flight, each on its own tensors and planned for its share of the GPU
+            share = sc.plan_opts(target_items=slots)
+            pipe_plans[name] = [sc.st_conv_plan(cold_descs[i], share, keep=keep) for i in range(depth)]
+            pipe_streams[name] = [torch.cuda.Stream() for _ in range(depth)]
+            pipe_turn[name] = 0
 
     def run(policy: str, stream):
         if policy == "fused":
             sc.st_conv_run(plan, stream)
-        elif policy == "fused_pipelined":
-            # two independent batches in flight: launches alternate between two sets of tensors on two streams
-            flip[0] ^= 1
-            sc.st_conv_run(pipe_plans[flip[0]], pipe[flip[0]])
+        elif policy in PIPELINED:
+            i = pipe_turn[policy] = (pipe_turn[policy] + 1) % len(pipe_plans[policy])
+            sc.st_conv_run(pipe_plans[policy][i], pipe_streams[policy][i])
         elif policy == "fused_cold":
             turn[0] = (turn[0] + 1) % (len(cold_plans) + 1)
             sc.st_conv_run(cold_plans[turn[0] - 1] if turn[0] else plan, stream)
@@ -121,9 +132,13 @@ def build_workload(cfg: int, copies: int = 1):
         else:
             sc.st_conv_run_plans_space_only(solo, [stream] + streams[1:])
 
-    return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan),
-                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans, pipe_plans),
-                                                      "retuned": True, "copies": copies, "pipelined": copies > 1}
+    def new_streams(policy):
+        if policy in pipe_streams:
+            pipe_streams[policy] = [torch.cuda.Stream() for _ in pipe_streams[policy]]
+
+    return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan), "new_streams": new_streams,
+                                                      "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans, pipe_plans, pipe_streams),
+                                                      "retuned": True, "copies": copies, "pipelined": sorted(pipe_plans)}
 
 
 def time_policy(run, policy: str, steps: int, warmup: int):
@@ -505,7 +520,7 @@ def main():
 
     def measure(cfg: int, k: int, w: int):
         # enough copies of the tensors to exceed the 256 MB memory-side cache several times over
-        copies = 1 if cfg == 5 else max(3, int(1.2e9 // max(1, {1: 475e3, 2: 8.52e6, 3: 14.25e6, 4: 104.4e6}[cfg])))
+        copies = 1 if cfg == 5 else max(4, int(1.2e9 // max(1, {1: 475e3, 2: 8.52e6, 3: 14.25e6, 4: 104.4e6}[cfg])))
         copies = 1 if args.no_extras else min(copies, 160)
         run, flops, nbytes, n_launch, meta = build_workload(cfg, copies)
         out = {"flops": flops, "algorithmic_bytes": nbytes, "plan_build_us": round(meta["plan_build_us"], 1),
@@ -513,8 +528,8 @@ def main():
         pols = ["fused", "time_only", "space_only"] + (["time_only_retuned", "space_only_retuned"] if meta.get("retuned") else [])
         if meta.get("chains"):
             pols.append("space_only_chains")     # every tenant's whole chain on its own stream, joined once at the end
-        if meta.get("pipelined") and not args.no_extras:
-            pols.append("fused_pipelined")       # the fused launch with two independent batches in flight on two streams
+        if not args.no_extras:
+            pols += list(meta.get("pipelined", []))   # the fused launch with several independent batches in flight
         for pol in pols:
             wall_ms, ev_ms = time_policy(run, pol, k, w)
             if pol == "space_only_chains":
@@ -522,21 +537,28 @@ def main():
                 # this baseline the better of two tries
                 again = time_policy(run, pol, k, w)
                 wall_ms, ev_ms = min((wall_ms, ev_ms), again)
-            out[pol] = {"ms_per_step": wall_ms, "event_ms_per_step": None if pol == "fused_pipelined" else ev_ms,
+            if pol in PIPELINED:
+                # the same for the pipelined forms: a second try on freshly created streams
+                meta["new_streams"](pol)
+                again = time_policy(run, pol, k, w)
+                wall_ms, ev_ms = min((wall_ms, ev_ms), again)
+            out[pol] = {"ms_per_step": wall_ms, "event_ms_per_step": None if pol in PIPELINED else ev_ms,
                         "tflops": flops / (wall_ms * 1e-3) / 1e12}
         if cfg != 5:
             # free-running streams: per-tenant plans, no joins between steps (the strongest form of space-only)
-            plan, keep, streams, solo, cold_plans, _pipe_plans = meta["keep"]
-            wall_ms, ev_ms = time_free_running(solo, streams, k, w)
+            plan, keep, streams, solo, cold_plans = meta["keep"][:5]
+            wall_ms, ev_ms = min(time_free_running(solo, streams, k, w),
+                                 time_free_running(solo, [torch.cuda.Stream() for _ in streams], k, w))   # two sets of streams
             out["space_only_free"] = {"ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12}
             pols = pols + ["space_only_free"]
         # headline speed-ups are against the best form of each baseline (same tiles as the fused plan, each tenant
         # planned alone, streams joined per step or free-running)
         t_time = min(out[p]["ms_per_step"] for p in pols if p.startswith("time_only"))
         t_space = min(out[p]["ms_per_step"] for p in pols if p.startswith("space_only"))
-        t_fused = min(out[p]["ms_per_step"] for p in pols if p.startswith("fused"))
+        forms = [p for p in pols if p == "fused" or p in PIPELINED]
+        t_fused = min(out[p]["ms_per_step"] for p in forms)
         out["best"] = {"ms_per_step": t_fused, "tflops": flops / (t_fused * 1e-3) / 1e12,
-                       "form": min((p for p in pols if p.startswith("fused")), key=lambda p: out[p]["ms_per_step"])}
+                       "form": min(forms, key=lambda p: out[p]["ms_per_step"])}
         out["speedup_vs_time_only"] = t_time / t_fused
         out["speedup_vs_space_only"] = t_space / t_fused
         # one batch at a time: a single fused launch sequence against per-tenant launches that are joined every step
@@ -595,14 +617,16 @@ def main():
         "value": head["best"]["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": head["best"]["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
-        "config": {"workload": CONFIG_TEXT[args.config], "policy": ("fused space-time launch, cached plans, two independent batches in flight on two streams"
-                              if head["best"]["form"] == "fused_pipelined" else "fused space-time launch, cached plan"),
+        "config": {"workload": CONFIG_TEXT[args.config], "policy": ("fused space-time launch, cached plan" if head["best"]["form"] == "fused" else
+                              "fused space-time launch, cached plans, %d independent batches in flight on as many streams, "
+                              "each launch planned for %d workgroup slots" % PIPELINED[head["best"]["form"]]),
                    "tenants": __import__("paper_1901_00041_amd.synth", fromlist=["x"]).N_TENANTS[args.config]},
         "pct_bf16_mfma_peak": head["pct_bf16_mfma_peak"],
         "speedup_vs_time_only": head["speedup_vs_time_only"], "speedup_vs_space_only": head["speedup_vs_space_only"],
         "speedup_single_batch": head["speedup_single_batch"],
         "policies": {k: head[k] for k in ("fused", "fused_cold", "time_only", "space_only", "time_only_retuned",
-                                          "space_only_retuned", "space_only_chains", "space_only_free") if k in head},
+                                          "space_only_retuned", "space_only_chains", "space_only_free", "fused_pipelined",
+                                          "fused_pipelined4") if k in head},
         "launch_floor_us": floor_us, "plan_build_us": head["plan_build_us"], "work_items": head["work_items"],
         "gpu_max_hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "default(4)"),
         "roofline": roof,
