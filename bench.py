@@ -6,9 +6,10 @@
 A step is one pass of the hot path over one batch of synthetic input: every tenant's layer (or, for
 configuration 5, every tenant's 53-layer stack) executed through cached plans, inputs resident in HBM.
 Prints ONE JSON line.  `value` is aggregate conv TFLOP/s of the fused (space-time) policy on the
-headline workload, in its faster form: one launch sequence on one stream (`policies.fused`), or two
-independent batches in flight on two streams (`policies.fused_pipelined`; launches on one stream pay
-about 3 us of serialisation each that launches on different streams overlap).  `policies` and
+headline workload, in its fastest form: one launch sequence on one stream (`policies.fused`), or two or
+four independent batches in flight on as many streams, each launch planned for its share of the GPU
+(`policies.fused_pipelined`, `fused_pipelined4`; launches on one stream pay about 3 us of serialisation
+each that launches on different streams overlap).  `policies` and
 `per_config` carry every form of the time-only and space-only baselines (the fused plan's tiles or each
 tenant planned alone; streams joined every step or free-running) and the other configurations; speed-ups
 are best form against best form, `speedup_single_batch` one batch at a time.  `roofline` is measured
@@ -264,7 +265,7 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
               "square (256,256,256)": (1, 256, 16, 16, 256, 1, 1, 1, 0)}
     rs = [2, 4, 6, 8, 10, 14, 20, 28, 40, 56, 80, 120]
     streams = [torch.cuda.Stream() for _ in range(max(rs))]
-    pipe = [torch.cuda.Stream(), torch.cuda.Stream()]
+    pipe = [torch.cuda.Stream() for _ in range(max(d for d, _ in PIPELINED.values()))]
     out = {}
     for dtype, tdt in (("f32", torch.float32), ("bf16", torch.bfloat16)):
         for name, (N, C, H, W, K, R_, S_, st, pd) in shapes.items():
@@ -272,7 +273,7 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
             rows = []
             for r in rs:
                 keep, sets = [], []
-                for copy in range(2):        # two sets of tensors: the pipelined form keeps two batches in flight
+                for copy in range(max(d for d, _ in PIPELINED.values())):   # one set of tensors per batch in flight
                     descs = []
                     for t in range(r):
                         x = torch.randn((N, H, W, C), device="cuda").to(tdt)
@@ -283,17 +284,18 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                     sets.append(descs)
                 descs = sets[0]
                 plan = sc.st_conv_plan(descs, keep=keep)
-                plan2 = sc.st_conv_plan(sets[1], keep=keep)
+                pplans = {name: [sc.st_conv_plan(sets[i], sc.plan_opts(target_items=slots), keep=keep) for i in range(depth)]
+                          for name, (depth, slots) in PIPELINED.items()}
                 solo = [sc.st_conv_plan([d], keep=keep) for d in descs]
                 flops = int(sc.st_conv_plan_info(plan).flops)
-                flip = [0]
+                turn = {name: 0 for name in PIPELINED}
 
-                def run(policy, stream, plan=plan, plan2=plan2, solo=solo, r=r, flip=flip):
+                def run(policy, stream, plan=plan, pplans=pplans, solo=solo, r=r, turn=turn):
                     if policy == "fused":
                         sc.st_conv_run(plan, stream)
-                    elif policy == "fused_pipelined":
-                        flip[0] ^= 1
-                        sc.st_conv_run(plan2 if flip[0] else plan, pipe[flip[0]])
+                    elif policy in PIPELINED:
+                        i = turn[policy] = (turn[policy] + 1) % len(pplans[policy])
+                        sc.st_conv_run(pplans[policy][i], pipe[i])
                     elif policy == "time_only_same_tiles":
                         sc.st_conv_run_time_only(plan, stream)
                     elif policy == "space_only_same_tiles":
@@ -303,10 +305,10 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                     else:
                         sc.st_conv_run_plans_space_only(solo, [stream] + streams[1:r])
                 t = {pol: time_policy(run, pol, iters, warmup)[0]
-                     for pol in ("fused", "fused_pipelined", "time_only", "space_only", "time_only_same_tiles",
-                                 "space_only_same_tiles")}
+                     for pol in ["fused", "time_only", "space_only", "time_only_same_tiles", "space_only_same_tiles"] +
+                     list(PIPELINED)}
                 t["fused_single_stream"] = t["fused"]
-                t["fused"] = min(t["fused"], t["fused_pipelined"])               # the best form of every policy
+                t["fused"] = min([t["fused"]] + [t[p] for p in PIPELINED])         # the best form of every policy
                 t["space_only_free"] = time_free_running(solo, streams, iters, warmup)[0]
                 t["time_only"] = min(t["time_only"], t["time_only_same_tiles"])      # the best form of each baseline
                 t["space_only"] = min(t["space_only"], t["space_only_same_tiles"], t["space_only_free"])
