@@ -31,8 +31,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16/fp16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 matrix
 PEAK_HBM_GBS = 8000.0
-# forms of the fused policy with several independent batches in flight: (streams, workgroup slots the planner fills
-# per launch when that many launches share the GPU)
+# forms of the fused policy with several independent batches in flight: (depth of the st_pipeline, workgroup slots
+# the planner fills per launch when that many launches share the GPU = st_pipeline_slots(depth))
 PIPELINED = {"fused_pipelined": (2, 256), "fused_pipelined4": (4, 128)}
 PAPER_CONTEXT = {"space_time_over_space_only_geomean": 3.23, "space_time_over_time_only_geomean": [7.73, 7.71],
                  "hardware": "NVIDIA V100 (AWS p3), fp32 SGEMM M=256 N=128 K=1152, 2<=R<=120",
@@ -67,15 +67,16 @@ def build_workload(cfg: int, copies: int = 1):
             depth, slots = PIPELINED[policy]
             if policy not in twins:
                 twins[policy] = [ResNetStack(n_tenants=synth.N_TENANTS[5], cfg=5, seeded_weights=False,
-                                             plan_opts=sc.plan_opts(target_items=slots)) for _ in range(depth)]
-                pipes[policy] = [torch.cuda.Stream() for _ in range(depth)]
+                                             plan_opts=sc.plan_opts(target_items=slots))
+                                 for _ in range(depth)]
+                pipes[policy] = sc.Pipeline(depth)
                 turn5[policy] = 0
             i = turn5[policy] = (turn5[policy] + 1) % depth
-            twins[policy][i].run("fused", pipes[policy][i])
+            twins[policy][i].run("fused", pipes[policy].next())
 
         def new_streams5(policy):
             if policy in pipes:
-                pipes[policy] = [torch.cuda.Stream() for _ in pipes[policy]]
+                pipes[policy] = sc.Pipeline(pipes[policy].depth)
 
         return run5, stack.flops, stack.bytes, stack.n_launches, {"plan_build_us": stack.plan_build_us, "pipelined": sorted(PIPELINED),
                                                                        "new_streams": new_streams5,
@@ -110,9 +111,9 @@ def build_workload(cfg: int, copies: int = 1):
     for name, (depth, slots) in PIPELINED.items():
         if copies >= depth:
             # that many launches in flight, each on its own tensors and planned for its share of the GPU
-            share = sc.plan_opts(target_items=slots)
+            pipe_streams[name] = sc.Pipeline(depth)
+            share = sc.plan_opts(target_items=pipe_streams[name].slots)
             pipe_plans[name] = [sc.st_conv_plan(cold_descs[i], share, keep=keep) for i in range(depth)]
-            pipe_streams[name] = [torch.cuda.Stream() for _ in range(depth)]
             pipe_turn[name] = 0
 
     def run(policy: str, stream):
@@ -120,7 +121,7 @@ def build_workload(cfg: int, copies: int = 1):
             sc.st_conv_run(plan, stream)
         elif policy in PIPELINED:
             i = pipe_turn[policy] = (pipe_turn[policy] + 1) % len(pipe_plans[policy])
-            sc.st_conv_run(pipe_plans[policy][i], pipe_streams[policy][i])
+            pipe_streams[policy].run(pipe_plans[policy][i])
         elif policy == "fused_cold":
             turn[0] = (turn[0] + 1) % (len(cold_plans) + 1)
             sc.st_conv_run(cold_plans[turn[0] - 1] if turn[0] else plan, stream)
@@ -135,7 +136,7 @@ def build_workload(cfg: int, copies: int = 1):
 
     def new_streams(policy):
         if policy in pipe_streams:
-            pipe_streams[policy] = [torch.cuda.Stream() for _ in pipe_streams[policy]]
+            pipe_streams[policy] = sc.Pipeline(pipe_streams[policy].depth)
 
     return run, int(info.flops), int(info.bytes), 1, {"plan_build_us": statistics.median(t_plan), "new_streams": new_streams,
                                                       "n_items": int(info.n_items), "keep": (plan, keep, streams, solo, cold_plans, pipe_plans, pipe_streams),
@@ -265,7 +266,7 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
               "square (256,256,256)": (1, 256, 16, 16, 256, 1, 1, 1, 0)}
     rs = [2, 4, 6, 8, 10, 14, 20, 28, 40, 56, 80, 120]
     streams = [torch.cuda.Stream() for _ in range(max(rs))]
-    pipe = [torch.cuda.Stream() for _ in range(max(d for d, _ in PIPELINED.values()))]
+    pipes = {name: sc.Pipeline(depth) for name, (depth, _) in PIPELINED.items()}
     out = {}
     for dtype, tdt in (("f32", torch.float32), ("bf16", torch.bfloat16)):
         for name, (N, C, H, W, K, R_, S_, st, pd) in shapes.items():
@@ -295,7 +296,7 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                         sc.st_conv_run(plan, stream)
                     elif policy in PIPELINED:
                         i = turn[policy] = (turn[policy] + 1) % len(pplans[policy])
-                        sc.st_conv_run(pplans[policy][i], pipe[i])
+                        pipes[policy].run(pplans[policy][i])
                     elif policy == "time_only_same_tiles":
                         sc.st_conv_run_time_only(plan, stream)
                     elif policy == "space_only_same_tiles":

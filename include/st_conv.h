@@ -208,6 +208,25 @@ st_status st_plan_cache_get(st_plan_cache* cache, const st_conv_desc* descs, int
 st_status st_plan_cache_get_stats(const st_plan_cache* cache, st_plan_cache_stats* out);
 void st_plan_cache_destroy(st_plan_cache* cache);
 
+/* Several independent batches in flight.  Launches queued on one stream run strictly one after the other, and
+ * each pays the drain of the launch before it, the cache write-back and invalidate between them and the start-up
+ * of the next (about 3 us here); launches on different streams overlap all of that.  A pipeline is a ring of
+ * `depth` streams (default priority, created here, destroyed with it): st_pipeline_next hands out the stream for
+ * the next batch, round-robin; the caller queues that batch's launches on it (one st_conv_run, or a whole chain
+ * of dependent layers) with tensors no batch still in flight uses.  st_pipeline_slots(depth) is the
+ * st_plan_opts.target_items to plan such launches with: when `depth` launches share the GPU, fewer and larger
+ * work items beat filling the whole chip once per launch (0 = the planner's default, for depth 1).  This is the
+ * space-time trade-off of Section 4 one level up: how much of the GPU one fused launch spans against how many
+ * fused launches overlap in time.  st_pipeline_sync waits for every stream of the ring. */
+typedef struct st_pipeline st_pipeline;
+st_status st_pipeline_create(int32_t depth, st_pipeline** out_pipeline);
+int32_t st_pipeline_slots(int32_t depth);
+st_status st_pipeline_next(st_pipeline* pipeline, void** out_stream);
+/* st_pipeline_next followed by st_conv_run of `plan` on that stream. */
+st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan);
+st_status st_pipeline_sync(st_pipeline* pipeline);
+void st_pipeline_destroy(st_pipeline* pipeline);
+
 /* Introspection (used by the bit-exact work-list tests and by reports). */
 st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out);
 st_status st_conv_plan_tenant_info(const st_plan* plan, int32_t tenant, st_tenant_info* out);

@@ -932,6 +932,71 @@ extern "C" void st_plan_cache_destroy(st_plan_cache* cache) {
   delete cache;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// pipeline: several independent batches in flight
+// ---------------------------------------------------------------------------------------------------
+struct st_pipeline {
+  std::vector<hipStream_t> streams;
+  size_t next = 0;
+};
+
+extern "C" st_status st_pipeline_create(int32_t depth, st_pipeline** out_pipeline) {
+  if (!out_pipeline) return fail(ST_ERR_INVALID_ARG, "out_pipeline is NULL");
+  *out_pipeline = nullptr;
+  if (depth < 1 || depth > 64) return fail(ST_ERR_INVALID_ARG, "depth must be between 1 and 64");
+  st_pipeline* p = new (std::nothrow) st_pipeline();
+  if (!p) return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  for (int32_t i = 0; i < depth; ++i) {
+    hipStream_t s = nullptr;
+    const hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);     // default priority
+    if (e != hipSuccess) {
+      for (hipStream_t t : p->streams) (void)hipStreamDestroy(t);
+      delete p;
+      return hip_fail(e, "st_pipeline_create");
+    }
+    p->streams.push_back(s);
+  }
+  *out_pipeline = p;
+  return ST_OK;
+}
+
+extern "C" int32_t st_pipeline_slots(int32_t depth) {
+  // measured on configs 2-4: one launch in flight fills the planner's default; two share the chip as 256 slots
+  // each, four and more as 128 each (smaller shares lose to the fixed cost per work item)
+  if (depth <= 1) return 0;
+  return depth == 2 ? 256 : 128;
+}
+
+extern "C" st_status st_pipeline_next(st_pipeline* pipeline, void** out_stream) {
+  if (!pipeline || !out_stream) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  *out_stream = (void*)pipeline->streams[pipeline->next];
+  pipeline->next = (pipeline->next + 1) % pipeline->streams.size();
+  return ST_OK;
+}
+
+extern "C" st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan) {
+  if (!pipeline) return fail(ST_ERR_INVALID_ARG, "pipeline is NULL");
+  void* stream = nullptr;
+  st_status s = st_pipeline_next(pipeline, &stream);
+  if (s != ST_OK) return s;
+  return st_conv_run(plan, stream);
+}
+
+extern "C" st_status st_pipeline_sync(st_pipeline* pipeline) {
+  if (!pipeline) return fail(ST_ERR_INVALID_ARG, "pipeline is NULL");
+  for (hipStream_t s : pipeline->streams) ST_HIP(hipStreamSynchronize(s));
+  return ST_OK;
+}
+
+extern "C" void st_pipeline_destroy(st_pipeline* pipeline) {
+  if (!pipeline) return;
+  for (hipStream_t s : pipeline->streams) {
+    (void)hipStreamSynchronize(s);
+    (void)hipStreamDestroy(s);
+  }
+  delete pipeline;
+}
+
 extern "C" st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out) {
   if (!plan || !out) return fail(ST_ERR_INVALID_ARG, "NULL argument");
   out->n_tenants = (int32_t)plan->info.size();

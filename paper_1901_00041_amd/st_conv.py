@@ -20,6 +20,7 @@ DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
+           "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
@@ -103,6 +104,18 @@ def lib() -> ctypes.CDLL:
         L.st_plan_cache_get_stats.argtypes = [vp, P(st_plan_cache_stats)]
         L.st_plan_cache_destroy.argtypes = [vp]
         L.st_plan_cache_destroy.restype = None
+        L.st_pipeline_create.argtypes = [i32, P(vp)]
+        L.st_pipeline_create.restype = i32
+        L.st_pipeline_slots.argtypes = [i32]
+        L.st_pipeline_slots.restype = i32
+        L.st_pipeline_next.argtypes = [vp, P(vp)]
+        L.st_pipeline_next.restype = i32
+        L.st_pipeline_run.argtypes = [vp, vp]
+        L.st_pipeline_run.restype = i32
+        L.st_pipeline_sync.argtypes = [vp]
+        L.st_pipeline_sync.restype = i32
+        L.st_pipeline_destroy.argtypes = [vp]
+        L.st_pipeline_destroy.restype = None
         L.st_conv_run_plans_time_only.argtypes = [P(vp), i32, vp]
         L.st_conv_run_plans_space_only.argtypes = [P(vp), i32, P(vp), i32]
         L.st_conv_run_plans_on_streams.argtypes = [P(vp), i32, P(vp), i32]
@@ -278,6 +291,40 @@ def st_conv_plan_rebind_all(plan: Plan, descs: Sequence[st_conv_desc], stream=No
     _check(lib().st_conv_plan_rebind_all(plan.handle, arr, n, _stream(stream)), "st_conv_plan_rebind_all")
     if keep is not None and plan._keep is not None:
         plan._keep.append(keep)
+
+
+class Pipeline:
+    """Owns an st_pipeline*: a ring of streams for several independent batches in flight."""
+
+    def __init__(self, depth: int):
+        out = ctypes.c_void_p()
+        _check(lib().st_pipeline_create(depth, ctypes.byref(out)), "st_pipeline_create")
+        self.handle, self.depth = out.value, depth
+        self.slots = int(lib().st_pipeline_slots(depth))      # st_plan_opts.target_items for launches queued here
+
+    def next(self) -> int:
+        """Raw hipStream_t (as an integer) for the next batch."""
+        out = ctypes.c_void_p()
+        _check(lib().st_pipeline_next(self.handle, ctypes.byref(out)), "st_pipeline_next")
+        return int(out.value)
+
+    def run(self, plan) -> None:
+        """The plan's fused launch on the next stream of the ring."""
+        _check(lib().st_pipeline_run(self.handle, plan.handle), "st_pipeline_run")
+
+    def sync(self) -> None:
+        _check(lib().st_pipeline_sync(self.handle), "st_pipeline_sync")
+
+    def destroy(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            try:
+                _lib.st_pipeline_destroy(self.handle)
+            except Exception:      # interpreter shutdown
+                pass
+            self.handle = None
+
+    def __del__(self):
+        self.destroy()
 
 
 class PlanCache:

@@ -300,3 +300,35 @@ def test_plan_cache_dynamic_arrival(torch):
     st = cache.stats()
     assert st.hits >= 14 and st.misses >= 2 and st.size <= 4
     cache.destroy()
+
+
+def test_pipeline_keeps_independent_batches_in_flight(torch):
+    """A ring of four streams, four sets of tensors, plans made for a quarter of the GPU each: twelve launches queued
+    round-robin without waiting, one synchronisation, every batch's outputs checked against the oracle."""
+    from tests import helpers
+    pipe = sc.Pipeline(4)
+    assert pipe.slots == 128 and sc.Pipeline(1).slots == 0 and sc.Pipeline(2).slots == 256
+    batches = [helpers.make_tenants(2) for _ in range(4)]      # same seeded tensors, separate device buffers
+    plans = [helpers.plan_for(b, target_items=pipe.slots) for b in batches]
+    for rnd in range(3):
+        for b in batches:
+            for t in b:
+                t.clear()
+        torch.cuda.synchronize()
+        seen = set()
+        for i in range(4):
+            stream = pipe.next()
+            seen.add(stream)
+            sc.st_conv_run(plans[i], stream)
+        assert len(seen) == 4
+        pipe.sync()
+        if rnd == 2:          # the combined call: next stream + launch
+            for i in range(4):
+                pipe.run(plans[i])
+            pipe.sync()
+        for bi, b in enumerate(batches):
+            for ti, t in enumerate(b):
+                helpers.check_tenant(t, f"round {rnd} batch {bi} tenant {ti}")
+    with pytest.raises(sc.StError):
+        sc.Pipeline(0)
+    pipe.destroy()
