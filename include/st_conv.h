@@ -224,6 +224,9 @@ int32_t st_pipeline_slots(int32_t depth);
 st_status st_pipeline_next(st_pipeline* pipeline, void** out_stream);
 /* st_pipeline_next followed by st_conv_run of `plan` on that stream. */
 st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan);
+/* plans[0..n_plans) in order, `rounds` times over, each as st_pipeline_run: a native submission loop (the
+ * per-launch cost of a caller in an interpreted language is of the order of the launches themselves). */
+st_status st_pipeline_run_many(st_pipeline* pipeline, const st_plan* const* plans, int32_t n_plans, int32_t rounds);
 st_status st_pipeline_sync(st_pipeline* pipeline);
 void st_pipeline_destroy(st_pipeline* pipeline);
 

@@ -982,6 +982,17 @@ extern "C" st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan)
   return st_conv_run(plan, stream);
 }
 
+extern "C" st_status st_pipeline_run_many(st_pipeline* pipeline, const st_plan* const* plans, int32_t n_plans, int32_t rounds) {
+  if (!pipeline) return fail(ST_ERR_INVALID_ARG, "pipeline is NULL");
+  if (n_plans < 0 || rounds < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or a count is negative");
+  for (int32_t r = 0; r < rounds; ++r)
+    for (int32_t i = 0; i < n_plans; ++i) {
+      st_status s = st_pipeline_run(pipeline, plans[i]);
+      if (s != ST_OK) return s;
+    }
+  return ST_OK;
+}
+
 extern "C" st_status st_pipeline_sync(st_pipeline* pipeline) {
   if (!pipeline) return fail(ST_ERR_INVALID_ARG, "pipeline is NULL");
   for (hipStream_t s : pipeline->streams) ST_HIP(hipStreamSynchronize(s));

@@ -20,7 +20,7 @@ DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
-           "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_sync", "st_pipeline_destroy",
+           "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
@@ -112,6 +112,8 @@ def lib() -> ctypes.CDLL:
         L.st_pipeline_next.restype = i32
         L.st_pipeline_run.argtypes = [vp, vp]
         L.st_pipeline_run.restype = i32
+        L.st_pipeline_run_many.argtypes = [vp, P(vp), i32, i32]
+        L.st_pipeline_run_many.restype = i32
         L.st_pipeline_sync.argtypes = [vp]
         L.st_pipeline_sync.restype = i32
         L.st_pipeline_destroy.argtypes = [vp]
@@ -311,6 +313,10 @@ class Pipeline:
     def run(self, plan) -> None:
         """The plan's fused launch on the next stream of the ring."""
         _check(lib().st_pipeline_run(self.handle, plan.handle), "st_pipeline_run")
+
+    def run_many(self, plans, rounds: int = 1) -> None:
+        """plans in order, `rounds` times over, each on the next stream of the ring (one native loop)."""
+        _check(lib().st_pipeline_run_many(self.handle, _plan_array(plans), len(plans), rounds), "st_pipeline_run_many")
 
     def sync(self) -> None:
         _check(lib().st_pipeline_sync(self.handle), "st_pipeline_sync")

@@ -322,9 +322,12 @@ def test_pipeline_keeps_independent_batches_in_flight(torch):
             sc.st_conv_run(plans[i], stream)
         assert len(seen) == 4
         pipe.sync()
-        if rnd == 2:          # the combined call: next stream + launch
+        if rnd == 1:          # the combined call: next stream + launch
             for i in range(4):
                 pipe.run(plans[i])
+            pipe.sync()
+        if rnd == 2:          # the native loop: every plan twice over
+            pipe.run_many(plans, 2)
             pipe.sync()
         for bi, b in enumerate(batches):
             for ti, t in enumerate(b):
