@@ -18,7 +18,7 @@
  *     until it is destroyed or the tenant is rebound.  The library never frees them.
  *   - Layout: activations NHWC, weights KRSC (filter-major, channel fastest), outputs NHWC (N,P,Q,K).
  *   - Streams are hipStream_t passed as void*; NULL is the default stream.  Run calls are
- *     asynchronous, never synchronise and never allocate.
+ *     asynchronous, never synchronise and never allocate device memory.
  *   - Every function returns st_status; on failure no output argument is written (plan pointers are
  *     left NULL) and st_last_error_message() holds a thread-local description.
  *   - Same plan + same inputs => bitwise identical outputs on every run and under every issue policy
