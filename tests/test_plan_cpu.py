@@ -370,3 +370,20 @@ def test_planner_bisection_matches_exhaustive_search():
             finally:
                 os.environ.pop("ST_PLAN_EXHAUSTIVE", None)
             assert fast == slow
+
+
+def test_pipeline_share_table_and_argument_checks():
+    """The planner share that goes with a pipeline depth is a pure table; creating a ring needs a device, so without
+    one the call must fail with a status (never crash), and bad depths are rejected before any device call."""
+    assert [sc.lib().st_pipeline_slots(d) for d in (0, 1, 2, 3, 4, 8)] == [0, 0, 256, 128, 128, 128]
+    out = ctypes.c_void_p()
+    assert sc.lib().st_pipeline_create(0, ctypes.byref(out)) == sc.ST_ERR_INVALID_ARG and not out.value
+    assert sc.lib().st_pipeline_create(65, ctypes.byref(out)) == sc.ST_ERR_INVALID_ARG and not out.value
+    assert sc.lib().st_pipeline_create(2, None) == sc.ST_ERR_INVALID_ARG
+    st = sc.lib().st_pipeline_create(2, ctypes.byref(out))
+    if st == sc.ST_OK:
+        sc.lib().st_pipeline_destroy(out)
+    else:
+        assert st == sc.ST_ERR_DEVICE and not out.value and sc.lib().st_last_error_message()
+    assert sc.lib().st_pipeline_sync(None) == sc.ST_ERR_INVALID_ARG
+    assert sc.lib().st_pipeline_run(None, None) == sc.ST_ERR_INVALID_ARG
