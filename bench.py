@@ -625,6 +625,11 @@ def main():
     roof["kernel"] = "st_conv_kernel (fused launch)"
     roof["avg_launch_us"] = ev_s * 1e6
     roof["arithmetic_intensity"] = ai
+    # the same ratio at the job's throughput (several launches in flight overlap; a launch's own duration does not
+    # shrink): algorithmic bytes or flops per step / time per step of the best form
+    per_s = (head["flops"] / 1e12 if roof["bound"] == "mfma" else head["algorithmic_bytes"] / 1e9) / (head["best"]["ms_per_step"] * 1e-3)
+    roof["achieved_at_throughput"] = per_s
+    roof["frac_at_throughput"] = per_s / roof["peak"]
 
     per_config = {}
     if not args.no_sweep:
