@@ -633,7 +633,7 @@ extern "C" st_status st_conv_run_profiled(const st_plan* plan, void* hip_stream,
   if (n == 0) return ST_OK;
   uint64_t* d = nullptr;
   ST_HIP(hipMalloc((void**)&d, (size_t)n * kProfSlots * 8));
-  hipError_t e = hipMemset(d, 0, (size_t)n * kProfSlots * 8);
+  hipError_t e = hipMemsetAsync(d, 0, (size_t)n * kProfSlots * 8, (hipStream_t)hip_stream);   // ordered before the launch
   if (e == hipSuccess) e = (hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, n, hip_stream, d);
   if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
   if (e == hipSuccess) e = hipMemcpy(stamps, d, (size_t)n * kProfSlots * 8, hipMemcpyDeviceToHost);
