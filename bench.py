@@ -472,6 +472,18 @@ def isolation(reps: int = 30):
     return out
 
 
+def probes():
+    """Sustained rates of one compute unit's data paths (st_probe_cu_path): what a K step that stages its operands
+    through LDS can at best move per clock."""
+    from paper_1901_00041_amd import st_conv as sc
+    names = {0: "LDS write (ds_write_b128)", 1: "LDS read (ds_read_b128)", 2: "global -> VGPR -> LDS write, barrier per round",
+             3: "global -> LDS direct (global_load_lds_dwordx4)"}
+    out = {"mode": "probes", "unit": "bytes per shader clock per compute unit", "results": {}}
+    for m, name in names.items():
+        out["results"][name] = {"one_workgroup": sc.st_probe_cu_path(m, 1), "two_workgroups": sc.st_probe_cu_path(m, 2)}
+    return out
+
+
 def measured_traffic(cfg: int):
     """HBM bytes per fused launch from the committed counter summary (profiles/hbm_traffic.txt), or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
@@ -502,6 +514,7 @@ def main():
                     help="run a synthetic trace whose ready set of tenants changes every step, through the plan cache")
     ap.add_argument("--isolation", action="store_true",
                     help="per-tenant completion spread of identical tenants: fused launch vs space-only")
+    ap.add_argument("--probes", action="store_true", help="measure the compute unit's LDS and vector-memory path rates")
     ap.add_argument("--counters", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: only K fused steps of the workload and K launches of "
                          "a 64 MiB copy kernel (the known-traffic reference); prints a short JSON line")
@@ -528,6 +541,9 @@ def main():
         return
     if args.isolation:
         print(json.dumps(isolation()))
+        return
+    if args.probes:
+        print(json.dumps(probes()))
         return
     if args.counters:
         run, flops, nbytes, n_launch, meta = build_workload(args.config)

@@ -208,6 +208,13 @@ st_status st_plan_cache_get(st_plan_cache* cache, const st_conv_desc* descs, int
 st_status st_plan_cache_get_stats(const st_plan_cache* cache, st_plan_cache_stats* out);
 void st_plan_cache_destroy(st_plan_cache* cache);
 
+/* Measurement helper: sustained bytes per shader clock of one compute unit's data paths, with one 256-thread
+ * workgroup on one compute unit (workgroups_per_cu = 1) or two on every compute unit (2; the figure is then per
+ * compute unit, both workgroups together).  mode 0: LDS writes (16 bytes per lane); 1: LDS reads; 2: global load
+ * -> registers -> LDS write, with a barrier per round as a staged K step has; 3: global loads straight into LDS.
+ * Synchronous; allocates and frees its own buffers; takes a few milliseconds. */
+st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, double* bytes_per_clock);
+
 /* Several independent batches in flight.  Launches queued on one stream run strictly one after the other, and
  * each pays the drain of the launch before it, the cache write-back and invalidate between them and the start-up
  * of the next (about 3 us here); launches on different streams overlap all of that.  A pipeline is a ring of

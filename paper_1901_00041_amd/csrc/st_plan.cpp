@@ -1042,6 +1042,37 @@ extern "C" void st_conv_plan_destroy(st_plan* plan) {
   delete plan;
 }
 
+extern "C" st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, double* bytes_per_clock) {
+  if (!bytes_per_clock) return fail(ST_ERR_INVALID_ARG, "bytes_per_clock is NULL");
+  if (mode < 0 || mode > 3) return fail(ST_ERR_INVALID_ARG, "mode must be 0..3");
+  if (workgroups_per_cu < 1 || workgroups_per_cu > 2) return fail(ST_ERR_INVALID_ARG, "workgroups_per_cu must be 1 or 2");
+  const int wgs = workgroups_per_cu == 1 ? 1 : 2 * kNumCUs;      // one workgroup alone, or two on every compute unit
+  const int iters = 500;
+  char* src = nullptr;
+  uint64_t* clocks = nullptr;
+  uint32_t* sink = nullptr;
+  hipError_t e = hipMalloc((void**)&src, 64 * 65536);
+  if (e == hipSuccess) e = hipMalloc((void**)&clocks, (size_t)wgs * 8);
+  if (e == hipSuccess) e = hipMalloc((void**)&sink, (size_t)wgs * kThreads * 4);
+  if (e == hipSuccess) e = hipMemset(src, 1, 64 * 65536);
+  std::vector<uint64_t> host((size_t)wgs, 0);
+  for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {       // the second launch is the measurement
+    e = (hipError_t)launch_probe(mode, wgs, src, clocks, sink, iters, nullptr);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+  }
+  if (e == hipSuccess) e = hipMemcpy(host.data(), clocks, (size_t)wgs * 8, hipMemcpyDeviceToHost);
+  if (src) (void)hipFree(src);
+  if (clocks) (void)hipFree(clocks);
+  if (sink) (void)hipFree(sink);
+  if (e != hipSuccess) return hip_fail(e, "st_probe_cu_path");
+  double mean = 0.0;
+  for (uint64_t c : host) mean += (double)c;
+  mean /= (double)wgs;
+  const double bytes = (double)iters * 8.0 * kThreads * 16.0;       // per workgroup
+  *bytes_per_clock = bytes / mean * workgroups_per_cu;                // per compute unit
+  return ST_OK;
+}
+
 extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT, int32_t* k_step_bytes) {
   if (index < 0 || index >= kNumTileCfgs || !MT || !NT || !k_step_bytes)
     return fail(ST_ERR_INVALID_ARG, "tile index out of range or NULL output");

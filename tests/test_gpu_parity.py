@@ -335,3 +335,15 @@ def test_pipeline_keeps_independent_batches_in_flight(torch):
     with pytest.raises(sc.StError):
         sc.Pipeline(0)
     pipe.destroy()
+
+
+def test_cu_path_probes_are_sane(torch):
+    """The measurement helper returns positive rates, reads well above writes (the asymmetry the K-loop analysis rests
+    on), and rejects bad arguments."""
+    w1, r1 = sc.st_probe_cu_path(0, 1), sc.st_probe_cu_path(1, 1)
+    assert 8.0 < w1 < 1024.0 and 8.0 < r1 < 1024.0 and r1 > 1.5 * w1
+    assert 8.0 < sc.st_probe_cu_path(2, 2) < 1024.0 and 8.0 < sc.st_probe_cu_path(3, 2) < 1024.0
+    with pytest.raises(sc.StError):
+        sc.st_probe_cu_path(4, 1)
+    with pytest.raises(sc.StError):
+        sc.st_probe_cu_path(0, 3)
