@@ -615,6 +615,18 @@ def main():
         out["pct_bf16_mfma_peak"] = 100.0 * out["best"]["tflops"] / PEAK_BF16_TFLOPS
         if not args.no_extras:
             out["fused"].update(launch_percentiles(run, "fused", 100 if cfg == 5 else 300))
+        if cfg == 5 and not args.no_extras:
+            # tenants at different depths of the network (offsets spread evenly): every launch mixes eight different
+            # layers; the baselines issue the same launches' work per tenant-layer.  One cycle = the work of one pass.
+            stag = {}
+            for pol in ("fused", "time_only", "space_only"):
+                wall_ms, ev_ms = time_policy(run, pol + "_staggered", max(3, k // 2), 2)
+                stag[pol] = {"ms_per_step": wall_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12}
+            stag["speedup_vs_time_only"] = stag["time_only"]["ms_per_step"] / stag["fused"]["ms_per_step"]
+            stag["speedup_vs_space_only"] = stag["space_only"]["ms_per_step"] / stag["fused"]["ms_per_step"]
+            stag["offsets"] = list(meta["keep"].stagger_offsets)
+            stag["work_items"] = int(meta["keep"].n_items_staggered)
+            out["staggered"] = stag
         if meta.get("copies", 1) > 1:
             wall_ms, ev_ms = time_policy(run, "fused_cold", k, w)
             out["fused_cold"] = {"ms_per_step": wall_ms, "event_ms_per_step": ev_ms, "tflops": flops / (wall_ms * 1e-3) / 1e12,
@@ -683,6 +695,8 @@ def main():
         "roofline": roof,
         "paper_context": PAPER_CONTEXT,
     }
+    if "staggered" in head:
+        line["staggered"] = head["staggered"]
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.config)
     if per_config:

@@ -2,7 +2,9 @@
 scheduled layer by layer: step s of every tenant goes into one fused launch (one cached plan per step).
 Consecutive steps that do not depend on each other (a block's projection conv and its first 1x1 conv both
 read the block input) are co-scheduled: the fused policy issues them as one launch over both steps'
-descriptors.
+descriptors.  A second schedule keeps the tenants at DIFFERENT depths of the network (requests that arrived
+at different times): every fused launch then mixes as many different layer shapes as there are tenants (the heterogeneous
+case that the paper's application model, Section 2, sets aside as future work).
 
 Data flow per tenant (no batch-norm): stem conv + ReLU, 3x3/2 max-pool, then per bottleneck
 a = ReLU(conv1(x)), b = ReLU(conv2(a)), out = ReLU(conv3(b) + shortcut), shortcut = x or proj(x).
@@ -170,10 +172,57 @@ class ResNetStack:
             done.record(s)
             anchor.wait_event(done)
 
+    # ---- tenants at different depths ---------------------------------------------------------------
+    def staggered_groups(self, g: int):
+        """[(tenant, group index)] of global step g in the staggered schedule: tenant t runs group
+        (g + offset_t) mod n_groups, i.e. the tenants sit at different depths of the network and every tenant
+        still walks its own layers in order (wrapping from the last layer to the first of its next image)."""
+        G = len(self.groups)
+        return [(t, (g + self.stagger_offsets[t]) % G) for t in range(self.n_tenants)]
+
+    def build_staggered(self, offsets=None) -> None:
+        """Plans for the steady state of a server whose tenants' requests arrived at different times: one fused
+        launch per global step over every tenant's CURRENT group of layers, which differ in shape from tenant to
+        tenant.  offsets default to an even spread over the depth of the network."""
+        G = len(self.groups)
+        self.stagger_offsets = list(offsets) if offsets is not None else [(t * G) // self.n_tenants for t in range(self.n_tenants)]
+        assert len(self.stagger_offsets) == self.n_tenants
+        self.staggered_plans = []
+        for g in range(G):
+            descs = [self._step_descs[i][t] for t, gi in self.staggered_groups(g) for i in self.groups[gi]]
+            self.staggered_plans.append(sc.st_conv_plan(descs, self._plan_opts))
+        self.n_items_staggered = sum(int(sc.st_conv_plan_info(p).n_items) for p in self.staggered_plans)
+
+    def run_staggered_step(self, g: int, stream=None, policy: str = "fused") -> None:
+        """Global step g of the staggered schedule (build_staggered first): one fused launch, or the same work
+        items as one launch per tenant-layer on one stream (time_only) or on one stream each (space_only)."""
+        if policy == "fused":
+            sc.st_conv_run(self.staggered_plans[g], stream)
+        elif policy == "time_only":
+            sc.st_conv_run_time_only(self.staggered_plans[g], stream)
+        elif policy == "space_only":
+            sc.st_conv_run_space_only(self.staggered_plans[g], [stream] + self._streams[1:])
+        else:
+            raise ValueError(f"unknown policy {policy!r}")
+        for t, gi in self.staggered_groups(g):
+            for i in self.groups[gi]:
+                st = self.steps[i]
+                if st.pool_after:
+                    s = st.shape
+                    sc.st_maxpool_nhwc(self.buf[st.dst][t], self.buf[st.pool_dst][t], s.N, s.P, s.Q, s.K, 3, 2, 1, "bf16",
+                                       stream)
+
     def run(self, policy: str = "fused", stream=None) -> None:
         if policy == "fused":
             for gi in range(len(self.groups)):
                 self.run_group(gi, stream)
+            return
+        if policy.endswith("_staggered"):
+            # one cycle: every tenant advances through all its groups once, so the work equals one lock-step pass
+            if not hasattr(self, "staggered_plans"):
+                self.build_staggered()
+            for g in range(len(self.groups)):
+                self.run_staggered_step(g, stream, policy[: -len("_staggered")])
             return
         if policy == "space_only_chains":
             self.run_chains(stream)

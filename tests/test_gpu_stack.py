@@ -129,3 +129,88 @@ def test_resnet50_stack_full_size_sampled():
                 f"step {i} {st.name} tenant {t}: max err {err.max():.3e}"
             worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
     print(f"full-size stack, sampled: worst relative error {worst:.3e}")
+
+
+def test_staggered_schedule_matches_lockstep_bitwise():
+    """Tenants kept at different depths of the network (every launch mixes different layers) walk the same chain
+    of layers as in lock-step: with the tile shape fixed, so that each layer sums in the same order under both
+    schedules, every tenant's network output is bitwise the lock-step one."""
+    import torch
+    from paper_1901_00041_amd.stack import ResNetStack
+    n_tenants = 3
+    stack = ResNetStack(n_tenants=n_tenants, plan_opts=sc.plan_opts(tile_cfg=4, split_k=1))
+    G = len(stack.groups)
+    last = stack.steps[-1]
+    s = last.shape
+    stack.run("fused")
+    torch.cuda.synchronize()
+    want = [stack.view(last.dst, t, s.N, s.P, s.Q, s.K).clone() for t in range(n_tenants)]
+    assert all(float(w.float().abs().max()) > 0 for w in want)
+    for i, b in stack.buf.items():
+        if i != 0:
+            b.zero_()                      # nothing of the lock-step pass is left but the network inputs
+    stack.build_staggered(offsets=[0, 17, 40])
+    assert [gi for _, gi in stack.staggered_groups(0)] == [0, 17, 40]
+    assert [gi for _, gi in stack.staggered_groups(G - 17)] == [G - 17, 0, 23]
+    got = {}
+    for cycle in range(2):
+        for g in range(G):
+            stack.run_staggered_step(g)
+            if cycle == 1:
+                for t, gi in stack.staggered_groups(g):
+                    if gi == G - 1:        # the tenant has just finished a whole image that it started in cycle 0
+                        got[t] = stack.view(last.dst, t, s.N, s.P, s.Q, s.K).clone()
+    torch.cuda.synchronize()
+    assert sorted(got) == list(range(n_tenants))
+    for t in range(n_tenants):
+        assert torch.equal(got[t], want[t]), f"tenant {t}"
+
+
+def test_staggered_schedule_layerwise_sampled():
+    """Teacher-forced parity of the launches that mix different layers: for every global step of the staggered
+    schedule, sampled outputs of every tenant's current layers against the oracle on the tensors that launch read."""
+    import torch
+    from oracle import oracle
+    from paper_1901_00041_amd.stack import ResNetStack
+    n_tenants = 4
+    stack = ResNetStack(n_tenants=n_tenants)
+    stack.run("fused")                      # sensible activations in every buffer before the schedule starts mid-network
+    stack.build_staggered()
+    offs = stack.stagger_offsets
+    assert len(set(offs)) == n_tenants
+    G = len(stack.groups)
+    rng = np.random.default_rng(77)
+    worst = 0.0
+    for g in range(G):
+        picks = {}
+        members = stack.staggered_groups(g)
+        assert sorted(t for t, _ in members) == list(range(n_tenants))
+        t_check = g % n_tenants                      # one tenant's layers checked per launch (every layer shape gets its turn)
+        for t, gi in members:
+            if t != t_check:
+                continue
+            for i in stack.groups[gi]:
+                st = stack.steps[i]
+                s = st.shape
+                idx = np.stack([rng.integers(s.N, size=64), rng.integers(s.K, size=64), rng.integers(s.P, size=64),
+                                rng.integers(s.Q, size=64)], axis=1).astype(np.int32)
+                x = _nchw(stack.view(st.src, t, s.N, s.H, s.W, s.C))
+                r = _nchw(stack.view(st.res, t, s.N, s.P, s.Q, s.K)) if st.res is not None else None
+                picks[(i, t)] = (idx, x, r)
+        info = sc.st_conv_plan_info(stack.staggered_plans[g])
+        assert info.n_tenants == sum(len(stack.groups[gi]) for _, gi in members)
+        stack.run_staggered_step(g)
+        torch.cuda.synchronize()
+        for (i, t), (idx, x, r) in picks.items():
+            st = stack.steps[i]
+            s = st.shape
+            ref = oracle.conv2d_points(x, synth.gen_weight(5, t, st.index, s, 2.0), idx, s.stride, s.pad)
+            if r is not None:
+                ref = ref + r[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+            if st.relu:
+                ref = np.maximum(ref, 0.0)
+            got = _nchw(stack.view(st.dst, t, s.N, s.P, s.Q, s.K))[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+            err = np.abs(got - ref)
+            assert (err <= 1e-2 * (np.abs(ref) + 1.0)).all(), f"global step {g} tenant {t} step {st.name}: max err {err.max():.3e}"
+            worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
+    print(f"staggered schedule: worst relative error {worst:.3e}")
