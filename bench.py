@@ -481,7 +481,17 @@ def probes():
     out = {"mode": "probes", "unit": "bytes per shader clock per compute unit", "results": {}}
     for m, name in names.items():
         out["results"][name] = {"one_workgroup": sc.st_probe_cu_path(m, 1), "two_workgroups": sc.st_probe_cu_path(m, 2)}
+    out["chip"] = achievable_roofs()
     return out
+
+
+def achievable_roofs():
+    """What this chip reaches on a plain copy and on a register-only MFMA loop (st_probe_chip), beside the published
+    peaks the roofline is priced against."""
+    from paper_1901_00041_amd import st_conv as sc
+    return {"hbm_copy_GBps": sc.st_probe_chip(0) / 1e9, "mfma_bf16_TFLOPs": sc.st_probe_chip(1) / 1e12,
+            "mfma_f16_TFLOPs": sc.st_probe_chip(2) / 1e12, "mfma_f32_TFLOPs": sc.st_probe_chip(3) / 1e12,
+            "published": {"hbm_GBps": PEAK_HBM_GBS, "mfma_bf16_TFLOPs": PEAK_BF16_TFLOPS, "mfma_f32_TFLOPs": PEAK_F32_TFLOPS}}
 
 
 def measured_traffic(cfg: int):
@@ -656,6 +666,8 @@ def main():
     # the same ratio at the job's throughput (several launches in flight overlap; a launch's own duration does not
     # shrink): algorithmic bytes or flops per step / time per step of the best form
     per_s = (head["flops"] / 1e12 if roof["bound"] == "mfma" else head["algorithmic_bytes"] / 1e9) / (head["best"]["ms_per_step"] * 1e-3)
+    if not args.no_extras:
+        roof["achievable"] = achievable_roofs()
     roof["achieved_at_throughput"] = per_s
     roof["frac_at_throughput"] = per_s / roof["peak"]
 

@@ -215,6 +215,15 @@ void st_plan_cache_destroy(st_plan_cache* cache);
  * Synchronous; allocates and frees its own buffers; takes a few milliseconds. */
 st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, double* bytes_per_clock);
 
+/* Measurement helper: rates this chip actually reaches, to set beside the published peaks the roofline is
+ * priced against.  what 0: device-memory copy, bytes read plus bytes written per second (1 GiB to 1 GiB, far
+ * larger than the memory-side cache); 1 / 2 / 3: matrix-core floating-point operations per second of a
+ * register-only loop of the 32x32 MFMA the convolution tiles use, for bf16 / f16 / f32 inputs (fp32
+ * accumulation), two 256-thread workgroups on every compute unit.  *rate (host) receives bytes/s or FLOP/s.
+ * Synchronous on the null stream; allocates and frees its own buffers (2 GiB for what = 0); tens of
+ * milliseconds. */
+st_status st_probe_chip(int32_t what, double* rate);
+
 /* Several independent batches in flight.  Launches queued on one stream run strictly one after the other, and
  * each pays the drain of the launch before it, the cache write-back and invalidate between them and the start-up
  * of the next (about 3 us here); launches on different streams overlap all of that.  A pipeline is a ring of

@@ -1169,6 +1169,42 @@ int launch_probe(int mode, int workgroups, const void* src, uint64_t* clocks, ui
   return (int)hipGetLastError();
 }
 
+// Register-only MFMA loop: four independent accumulators per wavefront, operands never change, so nothing but the
+// matrix pipe limits it.  One call of Mma<DT, 32>::run is 32*32*16 multiply-adds for the 16-bit types and
+// 32*32*8 for fp32 (four 32x32x2 instructions).
+template <int DT>
+__global__ __launch_bounds__(kThreads) void st_probe_mfma_kernel(float* __restrict__ sink, int iters) {
+  typedef Mma<DT, 32> MMA;
+  const uint32_t seed = 0x3c003c00u + threadIdx.x;          // small finite values in every format
+  const u32x4 a = {seed, seed, seed, seed}, b = {seed ^ 1u, seed, seed, seed};
+  typename MMA::Acc acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
+#pragma unroll 1
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[u] = MMA::run(a, b, acc[u]);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += acc[u][e];
+  sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = sum;
+}
+
+int launch_probe_mfma(int dtype, int workgroups, float* sink, int iters, void* stream) {
+  const dim3 grid((unsigned)workgroups), block(kThreads);
+  switch (dtype) {
+    case ST_DT_BF16: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_BF16>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
+    case ST_DT_F16: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_F16>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
+    default: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_F32>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
+  }
+  return (int)hipGetLastError();
+}
+
 int launch_empty(void* stream) {
   hipLaunchKernelGGL(st_empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
   return (int)hipGetLastError();

@@ -1073,6 +1073,48 @@ extern "C" st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, d
   return ST_OK;
 }
 
+extern "C" st_status st_probe_chip(int32_t what, double* rate) {
+  if (!rate) return fail(ST_ERR_INVALID_ARG, "rate is NULL");
+  if (what < 0 || what > 3) return fail(ST_ERR_INVALID_ARG, "what must be 0..3");
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  float ms = 0.f;
+  double work = 0.0;      // bytes or floating-point operations of the timed launches
+  void* bufs[2] = {nullptr, nullptr};
+  const int reps = 5;
+  if (what == 0) {
+    // copy between two buffers that together exceed the memory-side cache several times over
+    const int64_t bytes = (int64_t)1 << 30;
+    if (e == hipSuccess) e = hipMalloc(&bufs[0], (size_t)bytes);
+    if (e == hipSuccess) e = hipMalloc(&bufs[1], (size_t)bytes);
+    if (e == hipSuccess) e = hipMemset(bufs[0], 1, (size_t)bytes);
+    if (e == hipSuccess) e = (hipError_t)launch_copy(bufs[0], bufs[1], bytes, nullptr);      // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = (hipError_t)launch_copy(bufs[0], bufs[1], bytes, nullptr);
+    work = 2.0 * (double)bytes * reps;       // every byte is read once and written once
+  } else {
+    const int dtype = what == 1 ? ST_DT_BF16 : what == 2 ? ST_DT_F16 : ST_DT_F32;
+    const int wgs = 2 * kNumCUs, iters = 4096;
+    if (e == hipSuccess) e = hipMalloc(&bufs[0], (size_t)wgs * kThreads * 4);
+    if (e == hipSuccess) e = (hipError_t)launch_probe_mfma(dtype, wgs, (float*)bufs[0], 64, nullptr);     // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = (hipError_t)launch_probe_mfma(dtype, wgs, (float*)bufs[0], iters, nullptr);
+    const double per_call = 2.0 * 32 * 32 * (dtype == ST_DT_F32 ? 8 : 16);      // one Mma<DT, 32>::run
+    work = (double)reps * wgs * (kThreads / 64) * iters * 4.0 * per_call;
+  }
+  if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return hip_fail(e, "st_probe_chip");
+  *rate = work / ((double)ms * 1e-3);
+  return ST_OK;
+}
+
 extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT, int32_t* k_step_bytes) {
   if (index < 0 || index >= kNumTileCfgs || !MT || !NT || !k_step_bytes)
     return fail(ST_ERR_INVALID_ARG, "tile index out of range or NULL output");

@@ -347,3 +347,14 @@ def test_cu_path_probes_are_sane(torch):
         sc.st_probe_cu_path(4, 1)
     with pytest.raises(sc.StError):
         sc.st_probe_cu_path(0, 3)
+
+
+def test_chip_probes_are_sane(torch):
+    """Achievable roofs: the copy runs below the published memory bandwidth and above a tenth of it; the MFMA loops
+    below the published matrix peaks and above a third of them; 16-bit inputs run far faster than fp32."""
+    copy = sc.st_probe_chip(0)
+    assert 0.8e12 < copy < 8.0e12
+    bf16, f16, f32 = sc.st_probe_chip(1), sc.st_probe_chip(2), sc.st_probe_chip(3)
+    assert 0.8e15 < bf16 < 2.6e15 and 0.8e15 < f16 < 2.6e15 and 50e12 < f32 < 160e12
+    with pytest.raises(sc.StError):
+        sc.st_probe_chip(4)
