@@ -426,6 +426,7 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   constexpr int SUBB = (MF == 32) ? 32 : 64;   // row bytes one MFMA sub-step consumes
   constexpr int NSUB = KB / SUBB;
   static_assert(D % 2 == 0, "D must be even so that register slots and LDS buffers are both static");
+  constexpr bool kOneBlockStep = (MT * NT >= 128 * 64);   // see issue()
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
   static_assert(WPX * WCH == 4 && WM % MF == 0 && WN % MF == 0, "bad tile shape");
@@ -492,18 +493,23 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   auto issue = [&](u32x4 (&qa)[A_IT], u32x4 (&qb)[B_IT]) {
     if constexpr (!GENERIC) {
       const bool kin = k_elem < klimit;
+      // filter tap (kr, ksx) and offset of this thread's vector
       int kr, ksx, koff;
-      if (T.tap_uniform) {
-        // C is a multiple of the K step: the whole step lies in one filter tap, found with scalar math
-        const int rs = fast_div(k_step0, T.magic_c, T.shift_c);
-        kr = fast_div(rs, T.magic_s, T.shift_s);
-        ksx = rs - kr * S;
-        koff = (kr * W + ksx) * C + (k_step0 - rs * C) + chunk * VEC;
-      } else {
+      if (kOneBlockStep || !T.tap_uniform) {
+        // per-lane form.  The large tiles use it always: without a branch the K step is a single basic block,
+        // and the compiler then overlaps the address arithmetic, the loads and the LDS writes with the MFMAs
+        // (a workgroup alone on its compute unit steps 18 % faster)
         const int rs = fast_div(k_elem, T.magic_c, T.shift_c);
         kr = fast_div(rs, T.magic_s, T.shift_s);
         ksx = rs - kr * S;
         koff = (kr * W + ksx) * C + (k_elem - rs * C);
+      } else {
+        // C is a multiple of the K step: the whole step lies in one filter tap, found with scalar math (the
+        // small tiles have few MFMAs to hide vector arithmetic behind)
+        const int rs = fast_div(k_step0, T.magic_c, T.shift_c);
+        kr = fast_div(rs, T.magic_s, T.shift_s);
+        ksx = rs - kr * S;
+        koff = (kr * W + ksx) * C + (k_step0 - rs * C) + chunk * VEC;
       }
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
