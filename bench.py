@@ -625,6 +625,20 @@ def main():
         out["pct_bf16_mfma_peak"] = 100.0 * out["best"]["tflops"] / PEAK_BF16_TFLOPS
         if not args.no_extras:
             out["fused"].update(launch_percentiles(run, "fused", 100 if cfg == 5 else 300))
+        if cfg == 5:
+            # glue inside the pass: the one max-pool launch over all tenants' stem outputs (the residual adds and
+            # ReLUs are in the conv epilogues).  Timed alone, back to back on one stream.
+            stack = meta["keep"]
+            st0 = stack.steps[0]
+            s0 = st0.shape
+
+            def pool_only(policy, stream):
+                sc.st_maxpool_nhwc(stack.buf[st0.dst], stack.buf[st0.pool_dst], stack.n_tenants * s0.N, s0.P, s0.Q, s0.K, 3, 2, 1,
+                                   "bf16", stream)
+            pool_ms = time_policy(pool_only, "pool", 200, 20)[1]
+            out["glue"] = {"maxpool_ms_per_pass": pool_ms, "conv_only_ms_per_pass": out["fused"]["event_ms_per_step"] - pool_ms,
+                           "end_to_end_ms_per_pass": out["fused"]["event_ms_per_step"],
+                           "note": "back-to-back pooling launches; inside the pass the launch also pays the stream's serialisation"}
         if cfg == 5 and not args.no_extras:
             # tenants at different depths of the network (offsets spread evenly): every launch mixes eight different
             # layers; the baselines issue the same launches' work per tenant-layer.  One cycle = the work of one pass.
@@ -707,8 +721,9 @@ def main():
         "roofline": roof,
         "paper_context": PAPER_CONTEXT,
     }
-    if "staggered" in head:
-        line["staggered"] = head["staggered"]
+    for extra in ("staggered", "glue"):
+        if extra in head:
+            line[extra] = head[extra]
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.config)
     if per_config:
