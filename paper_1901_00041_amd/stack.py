@@ -212,7 +212,53 @@ class ResNetStack:
                     sc.st_maxpool_nhwc(self.buf[st.dst][t], self.buf[st.pool_dst][t], s.N, s.P, s.Q, s.K, 3, 2, 1, "bf16",
                                        stream)
 
+    # ---- tenant groups: fused launches per group, groups side by side ---------------------------------
+    def build_tenant_groups(self, n_groups: int, opts=None) -> None:
+        """Split the tenants into n_groups groups of consecutive tenants.  Every group gets its own chain of fused
+        launches (one per layer group, over the group's tenants only), planned for its share of the GPU, and its own
+        stream: within a group the tenants advance in lock-step through one launch per layer, while the groups run
+        side by side and need not wait for each other's slowest tile between layers.  n_groups = 1 is the plain
+        fused policy, n_groups = n_tenants the chains form of space-only."""
+        assert 1 <= n_groups <= self.n_tenants
+        slots = {1: 0, 2: 256, 4: 128}.get(n_groups, max(32, 512 // n_groups))       # workgroup slots a launch is planned for
+        opts = opts if opts is not None else sc.plan_opts(target_items=slots)
+        bounds = [(g * self.n_tenants) // n_groups for g in range(n_groups + 1)]
+        self.tenant_groups = [list(range(bounds[g], bounds[g + 1])) for g in range(n_groups)]
+        self.tenant_group_plans = [[sc.st_conv_plan([self._step_descs[i][t] for i in lg for t in tg], opts)
+                                    for lg in self.groups] for tg in self.tenant_groups]
+
+    def run_tenant_groups(self, stream=None) -> None:
+        """One pass: every tenant group's chain of fused launches on its own stream; the streams fork from `stream`
+        at the start and join it at the end (build_tenant_groups first)."""
+        torch = self.torch
+        anchor = stream if stream is not None else torch.cuda.current_stream()
+        streams = [anchor] + self._streams[1:len(self.tenant_groups)]
+        start = torch.cuda.Event()
+        start.record(anchor)
+        for s in streams[1:]:
+            s.wait_event(start)
+        # issue layer by layer, round-robin over the groups, so that no stream's queue runs dry while another's fills
+        for gi, lg in enumerate(self.groups):
+            for g, tg in enumerate(self.tenant_groups):
+                sc.st_conv_run(self.tenant_group_plans[g][gi], streams[g])
+                for i in lg:
+                    st = self.steps[i]
+                    if st.pool_after:
+                        s = st.shape
+                        sc.st_maxpool_nhwc(self.buf[st.dst][tg[0]:tg[-1] + 1], self.buf[st.pool_dst][tg[0]:tg[-1] + 1],
+                                           len(tg) * s.N, s.P, s.Q, s.K, 3, 2, 1, "bf16", streams[g])
+        for s in streams[1:]:
+            done = torch.cuda.Event()
+            done.record(s)
+            anchor.wait_event(done)
+
     def run(self, policy: str = "fused", stream=None) -> None:
+        if policy.startswith("fused_groups"):
+            n = int(policy[len("fused_groups"):])
+            if getattr(self, "tenant_groups", None) is None or len(self.tenant_groups) != n:
+                self.build_tenant_groups(n)
+            self.run_tenant_groups(stream)
+            return
         if policy == "fused":
             for gi in range(len(self.groups)):
                 self.run_group(gi, stream)
