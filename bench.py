@@ -179,16 +179,14 @@ def time_free_running(plans, streams, steps: int, warmup: int):
     from paper_1901_00041_amd import st_conv as sc
     n = len(plans)
     use = streams[:n]
-    for _ in range(warmup):
-        sc.st_conv_run_plans_on_streams(plans, use)
+    sc.st_conv_run_plans_on_streams_many(plans, use, warmup)
     torch.cuda.synchronize()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     start.record(use[0])
     for s in use[1:]:
         s.wait_event(start)
-    for _ in range(steps):
-        sc.st_conv_run_plans_on_streams(plans, use)
+    sc.st_conv_run_plans_on_streams_many(plans, use, steps)      # the library's issue loop, as for the pipelined fused forms
     for s in use[1:]:
         done = torch.cuda.Event()
         done.record(s)
@@ -607,6 +605,22 @@ def main():
                 for _ in range(2):
                     meta["new_streams"](pol)
                     wall_ms, ev_ms = min((wall_ms, ev_ms), time_policy(run, pol, k, w))
+                if cfg != 5:
+                    # and the library's own issue loop (st_pipeline_run_many: no interpreter between launches, several
+                    # issuing threads), again on three sets of streams; exactly k steps each
+                    pipe_plans = meta["keep"][5][pol]
+                    depth = len(pipe_plans)
+                    for _ in range(3):
+                        pipe = sc.Pipeline(depth)
+                        pipe.run_many(pipe_plans, max(1, w // depth))
+                        pipe.sync()
+                        t0 = time.perf_counter()
+                        pipe.run_many(pipe_plans, k // depth)
+                        for i in range(k % depth):
+                            pipe.run(pipe_plans[i])
+                        pipe.sync()
+                        wall_ms = min(wall_ms, (time.perf_counter() - t0) * 1e3 / k)
+                        pipe.destroy()
             out[pol] = {"ms_per_step": wall_ms, "event_ms_per_step": None if pol in PIPELINED else ev_ms,
                         "tflops": flops / (wall_ms * 1e-3) / 1e12}
         if cfg != 5:

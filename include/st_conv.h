@@ -174,6 +174,11 @@ st_status st_conv_run_plans_space_only(const st_plan* const* plans, int32_t n_pl
  * layer as st_conv_run_plans_space_only does). */
 st_status st_conv_run_plans_on_streams(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
                                        int32_t n_streams);
+/* The same, `rounds` times over, as a native loop: the free-running baseline of Section 3 with the issue cost of
+ * st_pipeline_run_many (from 64 launches on, up to four host threads issue, each owning some of the streams, so the
+ * order on every stream is that of the serial loop; the call returns when all launches are issued). */
+st_status st_conv_run_plans_on_streams_many(const st_plan* const* plans, int32_t n_plans, void* const* hip_streams,
+                                            int32_t n_streams, int32_t rounds);
 
 /* Replace tenant pointers (the cached-plan path of Section 4: same shapes, new inputs).  NULL keeps
  * the current pointer.  Synchronous small upload on the default stream; not for use while a run of
@@ -241,7 +246,11 @@ st_status st_pipeline_next(st_pipeline* pipeline, void** out_stream);
 /* st_pipeline_next followed by st_conv_run of `plan` on that stream. */
 st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan);
 /* plans[0..n_plans) in order, `rounds` times over, each as st_pipeline_run: a native submission loop (the
- * per-launch cost of a caller in an interpreted language is of the order of the launches themselves). */
+ * per-launch cost of a caller in an interpreted language is of the order of the launches themselves).  From 64
+ * launches on, the launches are issued by up to four host threads (environment variable ST_PIPELINE_THREADS
+ * overrides the count; 1 = the calling thread only), each owning some of the ring's streams, so the order of the
+ * launches on every stream is that of the serial loop; the call returns when all are issued.  A launch costs
+ * the host about 2.3 us, more than a small fused launch needs once several are in flight. */
 st_status st_pipeline_run_many(st_pipeline* pipeline, const st_plan* const* plans, int32_t n_plans, int32_t rounds);
 st_status st_pipeline_sync(st_pipeline* pipeline);
 void st_pipeline_destroy(st_pipeline* pipeline);

@@ -19,7 +19,7 @@ ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
-           "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
+           "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_run_plans_on_streams_many", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
@@ -122,6 +122,8 @@ def lib() -> ctypes.CDLL:
         L.st_conv_run_plans_space_only.argtypes = [P(vp), i32, P(vp), i32]
         L.st_conv_run_plans_on_streams.argtypes = [P(vp), i32, P(vp), i32]
         L.st_conv_run_plans_on_streams.restype = i32
+        L.st_conv_run_plans_on_streams_many.argtypes = [P(vp), i32, P(vp), i32, i32]
+        L.st_conv_run_plans_on_streams_many.restype = i32
         L.st_conv_plan_info.argtypes = [vp, P(st_plan_info)]
         L.st_conv_plan_tenant_info.argtypes = [vp, i32, P(st_tenant_info)]
         L.st_conv_plan_worklist.argtypes = [vp, i32, P(P(st_work_item)), P(i64)]
@@ -282,6 +284,13 @@ def st_conv_run_plans_on_streams(plans, streams) -> None:
     hs = [_stream(s) for s in streams]
     arr = (ctypes.c_void_p * max(len(hs), 1))(*hs)
     _check(lib().st_conv_run_plans_on_streams(_plan_array(plans), len(plans), arr, len(hs)), "st_conv_run_plans_on_streams")
+
+
+def st_conv_run_plans_on_streams_many(plans, streams, rounds: int) -> None:
+    hs = [_stream(s) for s in streams]
+    arr = (ctypes.c_void_p * max(len(hs), 1))(*hs)
+    _check(lib().st_conv_run_plans_on_streams_many(_plan_array(plans), len(plans), arr, len(hs), rounds),
+           "st_conv_run_plans_on_streams_many")
 
 
 def st_conv_plan_rebind(plan: Plan, tenant: int, x=None, w=None, y=None, residual=None) -> None:

@@ -183,8 +183,20 @@ def test_per_tenant_plan_baselines(torch):
     _sync(torch)
     for i, t in enumerate(tenants):
         helpers.check_tenant(t, f"space-only, own plan, tenant {i}")
+    # free-running form, one call and the native loop over many rounds (the latter issues from several host threads)
+    for rounds in (0, 1, 50):
+        for t in tenants:
+            t.clear()
+        if rounds == 0:
+            sc.st_conv_run_plans_on_streams(plans, streams)
+        else:
+            sc.st_conv_run_plans_on_streams_many(plans, streams, rounds)
+        _sync(torch)
+        for i, t in enumerate(tenants):
+            helpers.check_tenant(t, f"free-running, {rounds} rounds, tenant {i}")
     sc.st_conv_run_plans_time_only([])
     sc.st_conv_run_plans_space_only([], streams)
+    sc.st_conv_run_plans_on_streams_many([], streams, 3)
 
 
 def test_split_k_workspace_is_not_stale_across_inputs(torch):
@@ -326,8 +338,10 @@ def test_pipeline_keeps_independent_batches_in_flight(torch):
             for i in range(4):
                 pipe.run(plans[i])
             pipe.sync()
-        if rnd == 2:          # the native loop: every plan twice over
+        if rnd == 2:          # the native loop: every plan twice over, then often enough for the issuing threads
             pipe.run_many(plans, 2)
+            pipe.sync()
+            pipe.run_many(plans, 40)
             pipe.sync()
         for bi, b in enumerate(batches):
             for ti, t in enumerate(b):
