@@ -171,6 +171,27 @@ def time_policy(run, policy: str, steps: int, warmup: int):
     return wall_ms / steps, e0.elapsed_time(e1) / steps
 
 
+def time_pipelined_native(pipe_plans, steps: int, warmup: int, tries: int = 3) -> float:
+    """ms per step of exactly `steps` fused launches queued round-robin over len(pipe_plans) streams by the library's own
+    issue loop (st_pipeline_run_many: no interpreter between launches, several issuing threads); best of `tries` freshly
+    created sets of streams."""
+    from paper_1901_00041_amd import st_conv as sc
+    depth = len(pipe_plans)
+    best = float("inf")
+    for _ in range(tries):
+        pipe = sc.Pipeline(depth)
+        pipe.run_many(pipe_plans, max(1, warmup // depth))
+        pipe.sync()
+        t0 = time.perf_counter()
+        pipe.run_many(pipe_plans, steps // depth)
+        for i in range(steps % depth):
+            pipe.run(pipe_plans[i])
+        pipe.sync()
+        best = min(best, (time.perf_counter() - t0) * 1e3 / steps)
+        pipe.destroy()
+    return best
+
+
 def time_free_running(plans, streams, steps: int, warmup: int):
     """Space-only without per-step joins: plan t is launched `steps` times back to back on stream t (round-robin issue
     over the streams), the streams fork from streams[0] once before the first launch and join it once after the
@@ -315,6 +336,8 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                 t = {pol: time_policy(run, pol, iters, warmup)[0]
                      for pol in ["fused", "time_only", "space_only", "time_only_same_tiles", "space_only_same_tiles"] +
                      list(PIPELINED)}
+                for pol in PIPELINED:
+                    t[pol] = min(t[pol], time_pipelined_native(pplans[pol], iters, warmup, tries=1))
                 t["fused_single_stream"] = t["fused"]
                 t["fused"] = min([t["fused"]] + [t[p] for p in PIPELINED])         # the best form of every policy
                 t["space_only_free"] = time_free_running(solo, streams, iters, warmup)[0]
@@ -327,6 +350,7 @@ def paper_sweep(iters: int = 200, warmup: int = 20):
                              "vs_time_only": t["time_only"] / t["fused"], "vs_space_only": t["space_only"] / t["fused"],
                              "vs_next_best": best_other / t["fused"],
                              "next_best": "time_only" if t["time_only"] <= t["space_only"] else "space_only"})
+            print(f"paper sweep: {dtype} {name} done", file=sys.stderr, flush=True)
             gm = lambda key: math.exp(sum(math.log(x[key]) for x in rows) / len(rows))
             out[f"{dtype} {name}"] = {"rows": rows, "geomean_vs_time_only": gm("vs_time_only"),
                                       "geomean_vs_space_only": gm("vs_space_only"), "geomean_vs_next_best": gm("vs_next_best"),
@@ -606,21 +630,7 @@ def main():
                     meta["new_streams"](pol)
                     wall_ms, ev_ms = min((wall_ms, ev_ms), time_policy(run, pol, k, w))
                 if cfg != 5:
-                    # and the library's own issue loop (st_pipeline_run_many: no interpreter between launches, several
-                    # issuing threads), again on three sets of streams; exactly k steps each
-                    pipe_plans = meta["keep"][5][pol]
-                    depth = len(pipe_plans)
-                    for _ in range(3):
-                        pipe = sc.Pipeline(depth)
-                        pipe.run_many(pipe_plans, max(1, w // depth))
-                        pipe.sync()
-                        t0 = time.perf_counter()
-                        pipe.run_many(pipe_plans, k // depth)
-                        for i in range(k % depth):
-                            pipe.run(pipe_plans[i])
-                        pipe.sync()
-                        wall_ms = min(wall_ms, (time.perf_counter() - t0) * 1e3 / k)
-                        pipe.destroy()
+                    wall_ms = min(wall_ms, time_pipelined_native(meta["keep"][5][pol], k, w))
             out[pol] = {"ms_per_step": wall_ms, "event_ms_per_step": None if pol in PIPELINED else ev_ms,
                         "tflops": flops / (wall_ms * 1e-3) / 1e12}
         if cfg != 5:
