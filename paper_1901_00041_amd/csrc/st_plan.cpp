@@ -770,18 +770,25 @@ static st_status issue_threaded(const st_plan* const* plans, int32_t n_plans, co
   int device = 0;
   ST_HIP(hipGetDevice(&device));
   std::vector<int> status((size_t)n_threads, (int)hipSuccess);
+  auto work = [&](int t) {
+    if (hipSetDevice(device) != hipSuccess) { status[(size_t)t] = (int)hipErrorInvalidDevice; return; }
+    for (int64_t L = 0; L < total; ++L) {
+      const size_t si = stream_of(L);
+      if ((int)(si % (size_t)n_threads) != t) continue;
+      const st_plan* plan = plans[L % n_plans];
+      const int e = launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), (void*)streams[si], nullptr);
+      if (e != (int)hipSuccess) { status[(size_t)t] = e; return; }
+    }
+  };
   std::vector<std::thread> workers;
-  for (int t = 0; t < n_threads; ++t)
-    workers.emplace_back([&, t]() {
-      if (hipSetDevice(device) != hipSuccess) { status[(size_t)t] = (int)hipErrorInvalidDevice; return; }
-      for (int64_t L = 0; L < total; ++L) {
-        const size_t si = stream_of(L);
-        if ((int)(si % (size_t)n_threads) != t) continue;
-        const st_plan* plan = plans[L % n_plans];
-        const int e = launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), (void*)streams[si], nullptr);
-        if (e != (int)hipSuccess) { status[(size_t)t] = e; return; }
-      }
-    });
+  int started = 1;                       // share 0 is the calling thread's
+  try {
+    for (; started < n_threads; ++started) workers.emplace_back(work, started);
+  } catch (...) {
+    // no more threads to be had: the calling thread takes the shares that have no thread of their own
+  }
+  work(0);
+  for (int t = started; t < n_threads; ++t) work(t);
   for (std::thread& w : workers) w.join();
   for (int e : status)
     if (e != (int)hipSuccess) return hip_fail((hipError_t)e, where);
