@@ -57,6 +57,8 @@ struct TenantDev {
   uint32_t magic_c, magic_s;
   int32_t shift_r, shift_nvp; // same for d = R and d = row_pitch/16 (row tile only)
   uint32_t magic_r, magic_nvp;
+  int32_t shift_pq, shift_q;  // same for d = P*Q and d = Q (pixel index -> image, row, column)
+  uint32_t magic_pq, magic_q;
   uint32_t x_bytes, w_bytes;  // buffer sizes for bounds-checked loads
   uint32_t y_bytes;           // size of y (and of the residual) in bytes
   int32_t rows_per_tile;      // row tile only: output rows per work item

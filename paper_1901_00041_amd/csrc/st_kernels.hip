@@ -466,9 +466,9 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
     const int m = m0 + row;
     const bool ok = (row < MT) && (m < T.M);
     const int mm = ok ? m : 0;
-    const int n = mm / T.PQ;
+    const int n = fast_div(mm, T.magic_pq, T.shift_pq);
     const int pq = mm - n * T.PQ;
-    const int p = pq / T.Q;
+    const int p = fast_div(pq, T.magic_q, T.shift_q);
     const int q = pq - p * T.Q;
     a_h0[i] = ok ? p * T.stride - T.pad : -(1 << 24);   // a dead row fails every bounds check
     a_w0[i] = q * T.stride - T.pad;

@@ -98,10 +98,12 @@ static st_status validate(const st_conv_desc& d, int t) {
 
 static int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-// Multiplier and shift with floor(n/d) == ((n*m) >> 31) >> L for every 0 <= n < 2^31 (1 <= d < 2^20).
+// Multiplier and shift with floor(n/d) == ((n*m) >> 31) >> L for every 0 <= n < 2^31 and 1 <= d < 2^31
+// (m = floor(2^(31+L)/d) + 1 fits 32 bits because d > 2^(L-1); m*d - 2^(31+L) <= d, so the error of n*m/2^(31+L)
+// against n/d stays below n/2^31 < 1 and cannot carry past the next integer).
 static void magic_for(int d, uint32_t* m, int32_t* L) {
   int l = 0;
-  while ((1 << l) < d) ++l;
+  while (((int64_t)1 << l) < (int64_t)d) ++l;
   *L = l;
   *m = (uint32_t)((((uint64_t)1) << (31 + l)) / (uint64_t)d + 1);
 }
@@ -593,6 +595,8 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.row_pitch = row_tile_pitch(d);
       magic_for(T.row_pitch / 16, &T.magic_nvp, &T.shift_nvp);
       magic_for(d.R, &T.magic_r, &T.shift_r);
+      magic_for(T.PQ, &T.magic_pq, &T.shift_pq);
+      magic_for(T.Q, &T.magic_q, &T.shift_q);
       T.x_bytes = (uint32_t)((int64_t)d.N * d.C * d.H * d.W * elem_size(d.in_dtype));
       T.w_bytes = (uint32_t)(ti.Ngemm * ti.Kgemm * elem_size(d.in_dtype));
       T.y_bytes = (uint32_t)(ti.M * ti.Ngemm * elem_size(d.out_dtype));
