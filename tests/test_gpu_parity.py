@@ -372,3 +372,66 @@ def test_chip_probes_are_sane(torch):
     assert 0.8e15 < bf16 < 2.6e15 and 0.8e15 < f16 < 2.6e15 and 50e12 < f32 < 160e12
     with pytest.raises(sc.StError):
         sc.st_probe_chip(4)
+
+
+def test_tensor_just_below_the_size_limit(torch):
+    """The largest input the library accepts: x just below 2^31 bytes (1 x 4000 x 4000 x 64 bf16 = 2.048e9 bytes), so
+    byte offsets use nearly the whole 32-bit range; y is 1.02e9 bytes of fp32.  Bands of output rows at the top, the
+    middle and the bottom of the image (the last addresses) are compared element by element with the oracle run on
+    the matching band of input rows (a 3x3 conv reads one row above and below)."""
+    from oracle import oracle
+    H = W = 4000
+    C, K = 64, 16
+    g = torch.Generator(device="cuda").manual_seed(190100041)
+    x = (torch.rand((1, H, W, C), device="cuda", generator=g) * 2 - 1).to(torch.bfloat16)
+    w = (torch.randn((K, 3, 3, C), device="cuda", generator=g) / (9 * C) ** 0.5).to(torch.bfloat16)
+    y = torch.full((1, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    assert x.numel() * 2 < 2 ** 31 and x.numel() * 2 > 0.95 * 2 ** 31
+    plan = sc.st_conv_plan([sc.make_desc(1, C, H, W, K, 3, 3, 1, 1, "bf16", "f32", x, w, y)], keep=[x, w, y])
+    assert int(sc.st_conv_plan_info(plan).flops) == 2 * H * W * K * 9 * C
+    sc.st_conv_run(plan)
+    _sync(torch)
+    assert bool(torch.isfinite(y).all()), "an output element was never written"
+    w64 = w.double().cpu().numpy().transpose(0, 3, 1, 2)
+    worst = 0.0
+    for a, b in ((0, 6), (1997, 2003), (H - 6, H)):
+        lo, hi = max(a - 1, 0), min(b + 1, H)
+        band = x[:, lo:hi].double().cpu().numpy().transpose(0, 3, 1, 2)
+        ref = oracle.conv2d(band, w64, 1, 1)[:, :, a - lo:b - lo, :]            # rows a..b-1 of the full result
+        got = y[:, a:b].double().cpu().numpy().transpose(0, 3, 1, 2)
+        err = np.abs(got - ref)
+        assert (err <= 1e-4 * (np.abs(ref) + 1.0)).all(), f"rows {a}..{b}: max err {err.max():.3e}"
+        worst = max(worst, float(err.max()))
+    print(f"maximum-size tensor: worst error {worst:.3e}")
+    # one element more per pixel row would cross the limit
+    with pytest.raises(sc.StError):
+        sc.st_conv_plan([sc.make_desc(1, C, H + 200, W, K, 3, 3, 1, 1, "bf16", "f32", x, w, y)], sc.plan_opts(host_only=1))
+
+
+DEGENERATE = [
+    ConvShape(1, 1, 1, 1, 1, 1, 1, 1, 0, "f32", "f32"),          # a single multiply
+    ConvShape(1, 1, 1, 1, 1, 1, 1, 1, 0, "bf16", "bf16"),
+    ConvShape(1, 8, 1, 1, 8, 1, 1, 1, 0, "bf16", "f32"),         # one pixel: a matrix-vector product
+    ConvShape(2, 16, 3, 3, 5, 3, 3, 5, 0, "f16", "f32"),         # stride larger than the image: one output pixel
+    ConvShape(1, 8, 2, 2, 3, 3, 3, 1, 3, "bf16", "f32"),         # padding wider than the image: most taps read zeros
+    ConvShape(1, 2, 1, 40, 1, 1, 1, 1, 0, "f32", "f32"),         # one row, one filter
+    ConvShape(1, 16, 5, 1, 4, 5, 1, 1, 2, "bf16", "f32"),        # one column, tall filter
+    ConvShape(3, 1, 6, 6, 2, 2, 2, 2, 0, "f32", "f32"),          # one channel
+]
+
+
+def test_degenerate_shapes(torch):
+    """Single pixels, single channels and filters, strides and paddings larger than the image: alone and fused."""
+    from tests import helpers
+    tenants = [helpers.Tenant(s, synth.gen_input(95, t, 0, s), synth.gen_weight(95, t, 0, s)) for t, s in enumerate(DEGENERATE)]
+    for t in tenants:                                   # each alone
+        sc.st_conv_run(helpers.plan_for([t]))
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"degenerate[{i}] alone {t.shape}")
+        t.clear()
+    plan = helpers.plan_for(tenants)                    # all in one launch
+    sc.st_conv_run(plan)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"degenerate[{i}] fused {t.shape}")
