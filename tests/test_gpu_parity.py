@@ -435,3 +435,16 @@ def test_degenerate_shapes(torch):
     _sync(torch)
     for i, t in enumerate(tenants):
         helpers.check_tenant(t, f"degenerate[{i}] fused {t.shape}")
+
+
+def test_many_tenants_in_one_launch(torch):
+    """300 small tenants (more than 255, more than there are compute units), distinct weights each, in one fused launch."""
+    from tests import helpers
+    shapes = [ConvShape(1, 16, 6, 5 + (t % 3), 8 + 8 * (t % 2), 3, 3, 1, 1, "bf16", "f32") for t in range(300)]
+    tenants = [helpers.Tenant(s, synth.gen_input(96, t, 0, s), synth.gen_weight(96, t, 0, s)) for t, s in enumerate(shapes)]
+    plan = helpers.plan_for(tenants)
+    assert int(sc.st_conv_plan_info(plan).n_tenants) == 300
+    sc.st_conv_run(plan)
+    _sync(torch)
+    for i, t in enumerate(tenants):
+        helpers.check_tenant(t, f"tenant {i} of 300")
