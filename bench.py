@@ -652,10 +652,11 @@ def main():
         out["speedup_vs_time_only"] = t_time / t_fused
         out["speedup_vs_space_only"] = t_space / t_fused
         # one batch at a time: a single fused launch sequence against per-tenant launches that are joined every step
+        t_single = min(out[p]["ms_per_step"] for p in ("fused", "fused_groups2") if p in out)
         out["speedup_single_batch"] = {
-            "vs_time_only": t_time / out["fused"]["ms_per_step"],
+            "vs_time_only": t_time / t_single,
             "vs_space_only": min(out[p]["ms_per_step"] for p in pols if p.startswith("space_only") and p not in
-                                 ("space_only_free", "space_only_chains")) / out["fused"]["ms_per_step"]}
+                                 ("space_only_free", "space_only_chains")) / t_single}
         out["pct_bf16_mfma_peak"] = 100.0 * out["best"]["tflops"] / PEAK_BF16_TFLOPS
         if not args.no_extras:
             out["fused"].update(launch_percentiles(run, "fused", 100 if cfg == 5 else 300))
