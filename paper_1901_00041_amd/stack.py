@@ -160,8 +160,14 @@ class ResNetStack:
         streams = [anchor] + self._streams[1:]
         for s in streams[1:]:
             s.wait_event(start)
+        # runs of steps without pooling go to the library's issue loop in one call (tenant t on stream t; the loop
+        # issues from several host threads, which this many small launches need: 424 per pass)
+        run: list = []
         for i, st in enumerate(self.steps):
-            sc.st_conv_run_plans_on_streams(self.solo_plans(i), streams)      # tenant t on stream t
+            run.extend(self.solo_plans(i))
+            if st.pool_after or i == len(self.steps) - 1:
+                sc.st_conv_run_plans_on_streams_many(run, streams, 1)
+                run = []
             if st.pool_after:
                 s = st.shape
                 for t in range(self.n_tenants):
