@@ -43,7 +43,9 @@ typedef enum {
 } st_status;
 
 typedef enum { ST_DT_F32 = 0, ST_DT_BF16 = 1, ST_DT_F16 = 2 } st_dtype;
-typedef enum { ST_LAYOUT_NHWC_KRSC = 0 } st_layout;
+/* Only ST_LAYOUT_NHWC_KRSC is implemented: the reduction index is then channel-fastest and contiguous in both
+ * operands.  ST_LAYOUT_NCHW_KCRS is named so that callers can ask for it and get ST_ERR_UNSUPPORTED. */
+typedef enum { ST_LAYOUT_NHWC_KRSC = 0, ST_LAYOUT_NCHW_KCRS = 1 } st_layout;
 enum { ST_EPI_RELU = 1u, ST_EPI_RESIDUAL = 2u };
 
 /* One tenant's layer.  y[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]
@@ -119,8 +121,8 @@ typedef struct st_plan_info {
 
 typedef struct st_plan st_plan; /* opaque */
 
-/* Section 4 ("the scheduler must dynamically schedule kernels as they arrive"): build the launch
- * plan for whatever set of problems is ready.  Validates every descriptor, derives P, Q and the
+/* Section 4 (kernels arrive at run time, so super-kernels cannot be built ahead of time): build the
+ * launch plan for whatever set of problems is ready.  Validates every descriptor, derives P, Q and the
  * im2col sizes, picks a tile shape and a split-K factor per tenant so that the launch fills the
  * 256 compute units, enumerates the work items, and uploads the tenant table and work lists.
  * n_tenants == 0 gives an empty plan whose runs are no-ops.  Host allocations and (unless
@@ -212,22 +214,6 @@ st_status st_plan_cache_get(st_plan_cache* cache, const st_conv_desc* descs, int
                             st_plan** out_plan, int32_t* out_hit);
 st_status st_plan_cache_get_stats(const st_plan_cache* cache, st_plan_cache_stats* out);
 void st_plan_cache_destroy(st_plan_cache* cache);
-
-/* Measurement helper: sustained bytes per shader clock of one compute unit's data paths, with one 256-thread
- * workgroup on one compute unit (workgroups_per_cu = 1) or two on every compute unit (2; the figure is then per
- * compute unit, both workgroups together).  mode 0: LDS writes (16 bytes per lane); 1: LDS reads; 2: global load
- * -> registers -> LDS write, with a barrier per round as a staged K step has; 3: global loads straight into LDS.
- * Synchronous; allocates and frees its own buffers; takes a few milliseconds. */
-st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, double* bytes_per_clock);
-
-/* Measurement helper: rates this chip actually reaches, to set beside the published peaks the roofline is
- * priced against.  what 0: device-memory copy, bytes read plus bytes written per second (1 GiB to 1 GiB, far
- * larger than the memory-side cache); 1 / 2 / 3: matrix-core floating-point operations per second of a
- * register-only loop of the 32x32 MFMA the convolution tiles use, for bf16 / f16 / f32 inputs (fp32
- * accumulation), two 256-thread workgroups on every compute unit.  *rate (host) receives bytes/s or FLOP/s.
- * Synchronous on the null stream; allocates and frees its own buffers (2 GiB for what = 0); tens of
- * milliseconds. */
-st_status st_probe_chip(int32_t what, double* rate);
 
 /* Several independent batches in flight.  Launches queued on one stream run strictly one after the other, and
  * each pays the drain of the launch before it, the cache write-back and invalidate between them and the start-up

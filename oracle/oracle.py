@@ -10,9 +10,8 @@ Functions and what pins each of them (tests/test_oracle_*.py, all CPU):
   dims                    the worked example of Section 4.1 (M=256, N=128, K=1152).
   round_bf16              all 65536 bfloat16 patterns round-trip; 10^6 float32 values against a
                           library cast; hand-written tie cases.
-  maxpool2d, relu, add    textbook definitions; brute force and library comparison.
-  run_resnet50_step       composition of the above (checked through its parts and the schedule
-                          invariants of a standard ResNet-50).
+  maxpool2d, relu         textbook definitions; brute force and library comparison.
+  conv_layer              conv2d, then + residual, then relu: composition of the above, nothing else.
 """
 from __future__ import annotations
 

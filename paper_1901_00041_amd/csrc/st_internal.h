@@ -71,8 +71,6 @@ static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment
 int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
                 uint64_t* prof_dev);
 int launch_empty(void* stream);
-int launch_probe_mfma(int dtype, int workgroups, float* sink, int iters, void* stream);
-int launch_probe(int mode, int workgroups, const void* src, uint64_t* clocks, uint32_t* sink, int iters, void* stream);
 int launch_copy(const void* src, void* dst, int64_t bytes, void* stream);
 int launch_maxpool(const void* x, void* y, int N, int H, int W, int C, int P, int Q, int win, int stride,
                    int pad, int dtype, void* stream);

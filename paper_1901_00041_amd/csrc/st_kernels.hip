@@ -1127,90 +1127,6 @@ int launch_copy(const void* src, void* dst, int64_t bytes, void* stream) {
   return (int)hipGetLastError();
 }
 
-// ---- probes of one compute unit's data paths (measurement helpers, not part of the convolution path) ------
-// One workgroup of 256 threads per compute unit slot issues `iters` rounds of eight 16-byte-per-lane operations of one
-// kind over a 32 KiB LDS window (conflict-free: consecutive lanes, consecutive 16 bytes) and reports the shader
-// clocks it took.  MODE 0: ds_write_b128; 1: ds_read_b128; 2: global load -> VGPR -> ds_write_b128 (with the
-// barrier a staged K step has); 3: global load straight into LDS.  Global sources are 64 KiB per workgroup,
-// re-read every round (cache resident).
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void st_probe_kernel(const char* __restrict__ g, uint64_t* __restrict__ clocks,
-                                                           uint32_t* __restrict__ sink, int iters) {
-  __shared__ __attribute__((aligned(16))) char lds[65536];
-  const int tid = threadIdx.x, wave = tid >> 6;
-  for (int i = tid; i < 65536 / 4; i += kThreads) ((uint32_t*)lds)[i] = (uint32_t)i;
-  __syncthreads();
-  const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds + (uint32_t)tid * 16u;
-  const char* src = g + (size_t)(blockIdx.x % 64) * 65536 + tid * 16;
-  u32x4 v = {(uint32_t)tid, 1u, 2u, 3u}, r = {0u, 0u, 0u, 0u};
-  const uint64_t t0 = __builtin_readcyclecounter();
-#pragma unroll 1
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if constexpr (MODE == 0) asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(base), "v"(v), "n"(u * 4096));
-      if constexpr (MODE == 1) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(base), "n"(u * 4096));
-      if constexpr (MODE == 2) *(u32x4*)(lds + u * 4096 + tid * 16) = *(const u32x4*)(src + u * 4096);
-      if constexpr (MODE == 3)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + u * 4096),
-                                         (__attribute__((address_space(3))) void*)(lds + u * 4096 + wave * 1024), 16, 0, 0);
-    }
-    if constexpr (MODE == 2) __syncthreads();
-  }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  __syncthreads();
-  const uint64_t t1 = __builtin_readcyclecounter();
-  if (tid == 0) clocks[blockIdx.x] = t1 - t0;
-  sink[blockIdx.x * kThreads + tid] = r[0] + v[1] + ((const uint32_t*)lds)[(tid * 7) & 16383];
-}
-
-int launch_probe(int mode, int workgroups, const void* src, uint64_t* clocks, uint32_t* sink, int iters, void* stream) {
-  const dim3 grid((unsigned)workgroups), block(kThreads);
-  switch (mode) {
-    case 0: hipLaunchKernelGGL(st_probe_kernel<0>, grid, block, 0, (hipStream_t)stream, (const char*)src, clocks, sink, iters); break;
-    case 1: hipLaunchKernelGGL(st_probe_kernel<1>, grid, block, 0, (hipStream_t)stream, (const char*)src, clocks, sink, iters); break;
-    case 2: hipLaunchKernelGGL(st_probe_kernel<2>, grid, block, 0, (hipStream_t)stream, (const char*)src, clocks, sink, iters); break;
-    default: hipLaunchKernelGGL(st_probe_kernel<3>, grid, block, 0, (hipStream_t)stream, (const char*)src, clocks, sink, iters); break;
-  }
-  return (int)hipGetLastError();
-}
-
-// Register-only MFMA loop: four independent accumulators per wavefront, operands never change, so nothing but the
-// matrix pipe limits it.  One call of Mma<DT, 32>::run is 32*32*16 multiply-adds for the 16-bit types and
-// 32*32*8 for fp32 (four 32x32x2 instructions).
-template <int DT>
-__global__ __launch_bounds__(kThreads) void st_probe_mfma_kernel(float* __restrict__ sink, int iters) {
-  typedef Mma<DT, 32> MMA;
-  const uint32_t seed = 0x3c003c00u + threadIdx.x;          // small finite values in every format
-  const u32x4 a = {seed, seed, seed, seed}, b = {seed ^ 1u, seed, seed, seed};
-  typename MMA::Acc acc[4];
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-#pragma unroll 1
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) acc[u] = MMA::run(a, b, acc[u]);
-  }
-  float sum = 0.f;
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sum += acc[u][e];
-  sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = sum;
-}
-
-int launch_probe_mfma(int dtype, int workgroups, float* sink, int iters, void* stream) {
-  const dim3 grid((unsigned)workgroups), block(kThreads);
-  switch (dtype) {
-    case ST_DT_BF16: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_BF16>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
-    case ST_DT_F16: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_F16>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
-    default: hipLaunchKernelGGL(st_probe_mfma_kernel<ST_DT_F32>, grid, block, 0, (hipStream_t)stream, sink, iters); break;
-  }
-  return (int)hipGetLastError();
-}
-
 int launch_empty(void* stream) {
   hipLaunchKernelGGL(st_empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
   return (int)hipGetLastError();

@@ -76,6 +76,8 @@ static st_status validate(const st_conv_desc& d, int t) {
     return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown in_dtype %d", t, d.in_dtype);
   if (d.out_dtype != ST_DT_F32 && d.out_dtype != d.in_dtype)
     return fail(ST_ERR_UNSUPPORTED, "tenant %d: out_dtype must be f32 or equal to in_dtype", t);
+  if (d.layout == ST_LAYOUT_NCHW_KCRS)
+    return fail(ST_ERR_UNSUPPORTED, "tenant %d: layout NCHW/KCRS is not implemented (tensors must be NHWC / KRSC)", t);
   if (d.layout != ST_LAYOUT_NHWC_KRSC) return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown layout %d", t, d.layout);
   if (d.epilogue & ~(uint32_t)(ST_EPI_RELU | ST_EPI_RESIDUAL))
     return fail(ST_ERR_UNSUPPORTED, "tenant %d: unknown epilogue bits 0x%x", t, d.epilogue);
@@ -764,6 +766,26 @@ extern "C" st_status st_conv_run_plans_space_only(const st_plan* const* plans, i
 // streams[stream_of(L)]; thread t issues the launches whose stream index is t mod n_threads, in sequence order, so
 // the order on every stream is that of a serial loop.  A launch costs the host about 2.3 us, more than a small
 // fused launch needs on the device once several are in flight.
+// A plan with a split-K workspace must not run on two streams at once (its partial tiles and arrival counters are
+// shared by all its runs).  stream_of(i) is the stream index that launch i of one round of the sequence goes to,
+// period = launches after which the (plan, stream) pattern repeats.
+template <class StreamOf>
+static st_status check_workspace_streams(const st_plan* const* plans, int32_t n_plans, int64_t period, StreamOf stream_of,
+                                         const char* where) {
+  for (int32_t i = 0; i < n_plans; ++i) {
+    if (!plans[i] || plans[i]->workspace_bytes == 0) continue;
+    long first = -1;
+    for (int64_t L = 0; L < period; ++L) {
+      if (plans[L % n_plans] != plans[i]) continue;
+      const long si = (long)stream_of(L);
+      if (first < 0) first = si;
+      else if (si != first)
+        return fail(ST_ERR_INVALID_ARG, "%s: plan %d owns a split-K workspace and would be queued on more than one stream", where, i);
+    }
+  }
+  return ST_OK;
+}
+
 template <class StreamOf>
 static st_status issue_threaded(const st_plan* const* plans, int32_t n_plans, const std::vector<hipStream_t>& streams,
                                 int64_t total, int n_threads, StreamOf stream_of, const char* where) {
@@ -811,6 +833,13 @@ extern "C" st_status st_conv_run_plans_on_streams_many(const st_plan* const* pla
   if (!hip_streams || n_streams <= 0) return fail(ST_ERR_INVALID_ARG, "need at least one stream");
   const int64_t total = (int64_t)rounds * n_plans;
   const size_t used = (size_t)std::min(n_plans, n_streams);
+  for (int32_t i = 0; i < n_plans; ++i)
+    if (!plans[i]) return fail(ST_ERR_INVALID_ARG, "plans[%d] is NULL", i);
+  {
+    st_status s = check_workspace_streams(plans, n_plans, n_plans, [=](int64_t L) { return (size_t)(L % n_streams); },
+                                          "st_conv_run_plans_on_streams_many");
+    if (s != ST_OK) return s;
+  }
   const int n_threads = issue_threads(used);
   if (total < 64 || n_threads < 2) {
     for (int32_t r = 0; r < rounds; ++r) {
@@ -828,6 +857,13 @@ extern "C" st_status st_conv_run_plans_on_streams(const st_plan* const* plans, i
                                                   int32_t n_streams) {
   if (n_plans < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or n_plans negative");
   if (!hip_streams || n_streams <= 0) return fail(ST_ERR_INVALID_ARG, "need at least one stream");
+  for (int32_t i = 0; i < n_plans; ++i)
+    if (!plans[i]) return fail(ST_ERR_INVALID_ARG, "plans[%d] is NULL", i);
+  {
+    st_status s = check_workspace_streams(plans, n_plans, n_plans, [=](int64_t L) { return (size_t)(L % n_streams); },
+                                          "st_conv_run_plans_on_streams");
+    if (s != ST_OK) return s;
+  }
   for (int32_t i = 0; i < n_plans; ++i) {
     st_status s = st_conv_run(plans[i], hip_streams[i % n_streams]);
     if (s != ST_OK) return s;
@@ -868,28 +904,46 @@ extern "C" st_status st_conv_plan_rebind_all(st_plan* plan, const st_conv_desc* 
     changed |= d.x != T.x || d.w != T.w || d.y != T.y || ((T.epilogue & ST_EPI_RESIDUAL) && d.residual != T.res);
   }
   if (!changed) return ST_OK;
+  // The new table is assembled in a copy; the plan's host mirrors are replaced only once the upload is queued, so a
+  // failed call leaves the plan describing what the device table still holds.
+  std::vector<TenantDev> next;
+  try {
+    next = plan->tenants;
+  } catch (const std::bad_alloc&) {
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
   for (int t = 0; t < n_tenants; ++t) {
     const st_conv_desc& d = descs[t];
-    TenantDev& T = plan->tenants[t];
+    TenantDev& T = next[t];
     T.x = d.x; T.w = d.w; T.y = d.y;
     if (T.epilogue & ST_EPI_RESIDUAL) T.res = d.residual;
+  }
+  if (!plan->host_only && n_tenants > 0) {
+    // stream-ordered upload from a pinned slot; a slot is reused only after the copy that read it has finished
+    const int slot = plan->stage_next;
+    const size_t bytes = next.size() * sizeof(TenantDev);
+    if (!plan->h_stage[slot]) ST_HIP(hipHostMalloc((void**)&plan->h_stage[slot], bytes, hipHostMallocDefault));
+    if (!plan->ev_stage[slot]) ST_HIP(hipEventCreateWithFlags(&plan->ev_stage[slot], hipEventDisableTiming));
+    if (plan->stage_used[slot]) ST_HIP(hipEventSynchronize(plan->ev_stage[slot]));
+    std::memcpy(plan->h_stage[slot], next.data(), bytes);
+    ST_HIP(hipMemcpyAsync(plan->d_tenants, plan->h_stage[slot], bytes, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+    plan->stage_next = (slot + 1) % st_plan::kStageSlots;
+    plan->stage_used[slot] = true;      // the copy is queued: from here on the slot must not be rewritten before it ran
+    plan->tenants.swap(next);
+    for (int t = 0; t < n_tenants; ++t) {
+      const TenantDev& T = plan->tenants[t];
+      st_conv_desc& mine = plan->descs[t];
+      mine.x = T.x; mine.w = T.w; mine.y = T.y; mine.residual = T.res;
+    }
+    ST_HIP(hipEventRecord(plan->ev_stage[slot], (hipStream_t)hip_stream));
+    return ST_OK;
+  }
+  plan->tenants.swap(next);
+  for (int t = 0; t < n_tenants; ++t) {
+    const TenantDev& T = plan->tenants[t];
     st_conv_desc& mine = plan->descs[t];
     mine.x = T.x; mine.w = T.w; mine.y = T.y; mine.residual = T.res;
   }
-  if (plan->host_only || n_tenants == 0) return ST_OK;
-  // stream-ordered upload from a pinned slot; a slot is reused only after the copy that read it has finished
-  const int slot = plan->stage_next;
-  plan->stage_next = (slot + 1) % st_plan::kStageSlots;
-  const size_t bytes = plan->tenants.size() * sizeof(TenantDev);
-  if (!plan->h_stage[slot]) {
-    ST_HIP(hipHostMalloc((void**)&plan->h_stage[slot], bytes, hipHostMallocDefault));
-    ST_HIP(hipEventCreateWithFlags(&plan->ev_stage[slot], hipEventDisableTiming));
-  }
-  if (plan->stage_used[slot]) ST_HIP(hipEventSynchronize(plan->ev_stage[slot]));
-  std::memcpy(plan->h_stage[slot], plan->tenants.data(), bytes);
-  ST_HIP(hipMemcpyAsync(plan->d_tenants, plan->h_stage[slot], bytes, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
-  ST_HIP(hipEventRecord(plan->ev_stage[slot], (hipStream_t)hip_stream));
-  plan->stage_used[slot] = true;
   return ST_OK;
 }
 
@@ -1056,6 +1110,18 @@ extern "C" st_status st_pipeline_run_many(st_pipeline* pipeline, const st_plan* 
   if (n_plans < 0 || rounds < 0 || (n_plans > 0 && !plans)) return fail(ST_ERR_INVALID_ARG, "plans is NULL or a count is negative");
   const int64_t total = (int64_t)rounds * n_plans;
   const size_t depth = pipeline->streams.size();
+  for (int32_t i = 0; i < n_plans; ++i)
+    if (!plans[i]) return fail(ST_ERR_INVALID_ARG, "plans[%d] is NULL", i);
+  if (n_plans > 0 && rounds > 0) {
+    // launch L goes to stream (next + L) mod depth; over `rounds` rounds the pattern repeats after lcm(n_plans, depth)
+    int64_t a = n_plans, b = (int64_t)depth;
+    while (b) { const int64_t r = a % b; a = b; b = r; }
+    const int64_t period = std::min<int64_t>(total, (int64_t)n_plans / a * (int64_t)depth);
+    const size_t first0 = pipeline->next;
+    st_status s = check_workspace_streams(plans, n_plans, period, [=](int64_t L) { return (first0 + (size_t)L) % depth; },
+                                          "st_pipeline_run_many");
+    if (s != ST_OK) return s;
+  }
   const int n_threads = issue_threads(depth);
   if (total < 64 || n_threads < 2) {
     for (int32_t r = 0; r < rounds; ++r)
@@ -1120,79 +1186,6 @@ extern "C" void st_conv_plan_destroy(st_plan* plan) {
   if (!plan) return;
   destroy_device(plan);
   delete plan;
-}
-
-extern "C" st_status st_probe_cu_path(int32_t mode, int32_t workgroups_per_cu, double* bytes_per_clock) {
-  if (!bytes_per_clock) return fail(ST_ERR_INVALID_ARG, "bytes_per_clock is NULL");
-  if (mode < 0 || mode > 3) return fail(ST_ERR_INVALID_ARG, "mode must be 0..3");
-  if (workgroups_per_cu < 1 || workgroups_per_cu > 2) return fail(ST_ERR_INVALID_ARG, "workgroups_per_cu must be 1 or 2");
-  const int wgs = workgroups_per_cu == 1 ? 1 : 2 * kNumCUs;      // one workgroup alone, or two on every compute unit
-  const int iters = 500;
-  char* src = nullptr;
-  uint64_t* clocks = nullptr;
-  uint32_t* sink = nullptr;
-  hipError_t e = hipMalloc((void**)&src, 64 * 65536);
-  if (e == hipSuccess) e = hipMalloc((void**)&clocks, (size_t)wgs * 8);
-  if (e == hipSuccess) e = hipMalloc((void**)&sink, (size_t)wgs * kThreads * 4);
-  if (e == hipSuccess) e = hipMemset(src, 1, 64 * 65536);
-  std::vector<uint64_t> host((size_t)wgs, 0);
-  for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {       // the second launch is the measurement
-    e = (hipError_t)launch_probe(mode, wgs, src, clocks, sink, iters, nullptr);
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-  }
-  if (e == hipSuccess) e = hipMemcpy(host.data(), clocks, (size_t)wgs * 8, hipMemcpyDeviceToHost);
-  if (src) (void)hipFree(src);
-  if (clocks) (void)hipFree(clocks);
-  if (sink) (void)hipFree(sink);
-  if (e != hipSuccess) return hip_fail(e, "st_probe_cu_path");
-  double mean = 0.0;
-  for (uint64_t c : host) mean += (double)c;
-  mean /= (double)wgs;
-  const double bytes = (double)iters * 8.0 * kThreads * 16.0;       // per workgroup
-  *bytes_per_clock = bytes / mean * workgroups_per_cu;                // per compute unit
-  return ST_OK;
-}
-
-extern "C" st_status st_probe_chip(int32_t what, double* rate) {
-  if (!rate) return fail(ST_ERR_INVALID_ARG, "rate is NULL");
-  if (what < 0 || what > 3) return fail(ST_ERR_INVALID_ARG, "what must be 0..3");
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  hipError_t e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  float ms = 0.f;
-  double work = 0.0;      // bytes or floating-point operations of the timed launches
-  void* bufs[2] = {nullptr, nullptr};
-  const int reps = 5;
-  if (what == 0) {
-    // copy between two buffers that together exceed the memory-side cache several times over
-    const int64_t bytes = (int64_t)1 << 30;
-    if (e == hipSuccess) e = hipMalloc(&bufs[0], (size_t)bytes);
-    if (e == hipSuccess) e = hipMalloc(&bufs[1], (size_t)bytes);
-    if (e == hipSuccess) e = hipMemset(bufs[0], 1, (size_t)bytes);
-    if (e == hipSuccess) e = (hipError_t)launch_copy(bufs[0], bufs[1], bytes, nullptr);      // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = (hipError_t)launch_copy(bufs[0], bufs[1], bytes, nullptr);
-    work = 2.0 * (double)bytes * reps;       // every byte is read once and written once
-  } else {
-    const int dtype = what == 1 ? ST_DT_BF16 : what == 2 ? ST_DT_F16 : ST_DT_F32;
-    const int wgs = 2 * kNumCUs, iters = 4096;
-    if (e == hipSuccess) e = hipMalloc(&bufs[0], (size_t)wgs * kThreads * 4);
-    if (e == hipSuccess) e = (hipError_t)launch_probe_mfma(dtype, wgs, (float*)bufs[0], 64, nullptr);     // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = (hipError_t)launch_probe_mfma(dtype, wgs, (float*)bufs[0], iters, nullptr);
-    const double per_call = 2.0 * 32 * 32 * (dtype == ST_DT_F32 ? 8 : 16);      // one Mma<DT, 32>::run
-    work = (double)reps * wgs * (kThreads / 64) * iters * 4.0 * per_call;
-  }
-  if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
-  if (e == hipSuccess) e = hipEventSynchronize(e1);
-  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  for (void* b : bufs)
-    if (b) (void)hipFree(b);
-  if (e0) (void)hipEventDestroy(e0);
-  if (e1) (void)hipEventDestroy(e1);
-  if (e != hipSuccess) return hip_fail(e, "st_probe_chip");
-  *rate = work / ((double)ms * 1e-3);
-  return ST_OK;
 }
 
 extern "C" st_status st_tile_shape(int32_t index, int32_t* MT, int32_t* NT, int32_t* k_step_bytes) {

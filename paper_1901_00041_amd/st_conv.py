@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libst_conv.so")
 
 ST_OK, ST_ERR_INVALID_ARG, ST_ERR_UNSUPPORTED, ST_ERR_OUT_OF_MEMORY, ST_ERR_DEVICE = range(5)
 ST_DT_F32, ST_DT_BF16, ST_DT_F16 = 0, 1, 2
-ST_LAYOUT_NHWC_KRSC = 0
+ST_LAYOUT_NHWC_KRSC, ST_LAYOUT_NCHW_KCRS = 0, 1
 ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
@@ -23,7 +23,7 @@ EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_t
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
-           "st_launch_empty", "st_launch_copy", "st_probe_cu_path", "st_probe_chip", "st_status_string", "st_last_error_message"]
+           "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
 
 class st_conv_desc(ctypes.Structure):
@@ -132,10 +132,6 @@ def lib() -> ctypes.CDLL:
         L.st_tile_shape.argtypes = [i32, P(i32), P(i32), P(i32)]
         L.st_tile_count.argtypes = []
         L.st_maxpool_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
-        L.st_probe_cu_path.argtypes = [i32, i32, P(ctypes.c_double)]
-        L.st_probe_cu_path.restype = i32
-        L.st_probe_chip.argtypes = [i32, P(ctypes.c_double)]
-        L.st_probe_chip.restype = i32
         L.st_launch_empty.argtypes = [vp]
         L.st_launch_copy.argtypes = [vp, vp, i64, vp]
         L.st_status_string.argtypes = [i32]
@@ -306,18 +302,6 @@ def st_conv_plan_rebind_all(plan: Plan, descs: Sequence[st_conv_desc], stream=No
     _check(lib().st_conv_plan_rebind_all(plan.handle, arr, n, _stream(stream)), "st_conv_plan_rebind_all")
     if keep is not None and plan._keep is not None:
         plan._keep.append(keep)
-
-
-def st_probe_cu_path(mode: int, workgroups_per_cu: int) -> float:
-    out = ctypes.c_double()
-    _check(lib().st_probe_cu_path(mode, workgroups_per_cu, ctypes.byref(out)), "st_probe_cu_path")
-    return float(out.value)
-
-
-def st_probe_chip(what: int) -> float:
-    out = ctypes.c_double()
-    _check(lib().st_probe_chip(what, ctypes.byref(out)), "st_probe_chip")
-    return float(out.value)
 
 
 class Pipeline:

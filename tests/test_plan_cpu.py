@@ -26,12 +26,17 @@ def _host_plan(shapes, **opts):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "st_conv.h")).read()
-    declared = set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", header))
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert headers, "no public header"
+    declared = set()
+    for h in headers:
+        declared |= set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", open(h).read()))
+    assert not any("probe" in name for name in declared), "measurement probes do not belong in the public ABI"
     assert {"st_conv_plan", "st_conv_run", "st_conv_run_time_only", "st_conv_run_space_only"} <= declared
     lib = ctypes.CDLL(sc.LIB_PATH)
     for name in sorted(declared):
-        assert hasattr(lib, name), f"{name} is declared in st_conv.h but not exported"
+        assert hasattr(lib, name), f"{name} is declared in include/ but not exported"
     assert declared == set(sc.EXPORTS), (declared ^ set(sc.EXPORTS))
 
 
@@ -250,6 +255,8 @@ def test_validation_errors():
     assert status(d) == sc.ST_ERR_UNSUPPORTED
     d = _desc(good); d.layout = 3
     assert status(d) == sc.ST_ERR_UNSUPPORTED
+    d = _desc(good); d.layout = sc.ST_LAYOUT_NCHW_KCRS     # named in the header, not implemented
+    assert status(d) == sc.ST_ERR_UNSUPPORTED
     d = _desc(good); d.reserved = 1
     assert status(d) == sc.ST_ERR_INVALID_ARG
     assert status(_desc(synth.ConvShape(64, 1024, 256, 256, 8, 1, 1, 1, 0))) == sc.ST_ERR_UNSUPPORTED   # 2^32 elements
@@ -283,6 +290,26 @@ def test_rebind_checks_on_host_plan():
         sc.st_conv_plan_rebind(p, 2, x=0x50000)            # tenant out of range
     with pytest.raises(sc.StError):
         sc.st_conv_plan_rebind(p, 0, y=FAKE["x"])          # would alias
+
+
+def test_split_k_plan_on_two_streams_is_rejected():
+    """A plan that owns a split-K workspace must not be in flight on two streams: the multi-stream calls refuse it
+    before touching the device (host-only plans, made-up stream handles)."""
+    deep = synth.config_shapes(2)[3]                       # 49 x 512 x 4608: split-K
+    a = sc.st_conv_plan([_desc(deep)], sc.plan_opts(host_only=1, tile_cfg=5, split_k=4))
+    b = sc.st_conv_plan([_desc(synth.config_shapes(1)[0])], sc.plan_opts(host_only=1, split_k=1))
+    assert sc.st_conv_plan_info(a).workspace_bytes > 0 and sc.st_conv_plan_info(b).workspace_bytes == 0
+    streams = [0x1000, 0x2000]
+    for call in (lambda: sc.st_conv_run_plans_on_streams([a, a], streams),
+                 lambda: sc.st_conv_run_plans_on_streams_many([b, a, a], streams, 3)):
+        with pytest.raises(sc.StError) as e:
+            call()
+        assert e.value.status == sc.ST_ERR_INVALID_ARG and "workspace" in str(e.value)
+    # the same plan twice on ONE stream is ordered by the stream: accepted as far as this check goes (the host-only
+    # plan is then refused by the run itself)
+    with pytest.raises(sc.StError) as e:
+        sc.st_conv_run_plans_on_streams([a, b, a], [0x1000, 0x2000])      # a -> stream 0 both times
+    assert e.value.status == sc.ST_ERR_UNSUPPORTED
 
 
 def test_status_strings():
