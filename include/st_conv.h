@@ -133,6 +133,20 @@ st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, const st_pl
 /* Space-time policy (Section 4, Figure 6): one launch, grid = number of work items. */
 st_status st_conv_run(const st_plan* plan, void* hip_stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The plan's fused launch (as st_conv_run: same kernel, same work items, bitwise the same
+ * outputs) with the tenant table, the work list and the split-K workspace placed in a fixed device array of
+ * st_conv_noalloc_max_bytes() = 32 MiB that every GPU the library runs on holds until the process ends, instead
+ * of in memory the plan owns.  `plan` may be a host-only plan (st_plan_opts.host_only = 1: built without any
+ * device call) or an ordinary one; its tensors are the caller's, as always.  The call allocates no device or
+ * pinned memory and calls no copy routine: the tables travel inside the arguments of small launches queued on
+ * hip_stream ahead of the convolution launch (about one launch per 3.5 KB of tables), and the arrival counters
+ * are cleared by a fill launch.  Asynchronous.  ST_ERR_UNSUPPORTED when tables plus workspace exceed the array
+ * (checked before any device call).  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or several threads) race; calls queued on one stream are ordered by the stream. */
+st_status st_conv_run_noalloc(const st_plan* plan, void* hip_stream);
+int64_t st_conv_noalloc_max_bytes(void);
+
 /* The fused launch with in-kernel time stamps, for occupancy-per-tenant and latency reports (the
  * per-kernel monitoring Section 4 asks of the scheduler).  Synchronous, allocates a scratch buffer: a
  * diagnostic, not part of the run path.  stamps (HOST pointer) receives 8 uint64 per work item, in

@@ -71,6 +71,12 @@ static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment
 int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
                 uint64_t* prof_dev);
 int launch_empty(void* stream);
+// Allocation-free path: device address of the current GPU's fixed scratch array (looked up on first use per device),
+// host bytes -> device through kernel arguments (sizes rounded up to 16 bytes; dst 16-byte aligned), and a zero fill.
+constexpr int64_t kNoallocScratchBytes = (int64_t)32 << 20;
+int noalloc_scratch(void** out_ptr);
+int launch_poke(const void* host_src, int64_t bytes, void* dst_dev, void* stream);
+int launch_zero(void* dst_dev, int64_t bytes, void* stream);
 int launch_copy(const void* src, void* dst, int64_t bytes, void* stream);
 int launch_maxpool(const void* x, void* y, int N, int H, int W, int C, int P, int Q, int win, int stride,
                    int pad, int dtype, void* stream);

@@ -14,9 +14,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstring>
+#include <mutex>
 #include <utility>
 
 #include "st_internal.h"
+
+// Fixed scratch memory for the entry point that allocates nothing (st_conv_run_noalloc).  One array per GPU, held
+// from the moment the code object is loaded on that GPU until the process ends.  Host code never uses the array's
+// name as an address: the device address is looked up once per device (st::noalloc_scratch) and kept.
+static __device__ __align__(256) unsigned char scratch[st::kNoallocScratchBytes];
 
 namespace st {
 
@@ -1124,6 +1131,68 @@ int launch_copy(const void* src, void* dst, int64_t bytes, void* stream) {
   if (n16 <= 0) return 0;
   const unsigned blocks = (unsigned)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
   hipLaunchKernelGGL(st_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst, n16);
+  return (int)hipGetLastError();
+}
+
+// ---- the entry point that allocates nothing: tables and split-K workspace in the fixed array `scratch` -------
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Bytes that travel to the device inside the kernel arguments (a launch copies its arguments when it is issued, so
+// the host buffer is free again as soon as the launch call returns, and no copy routine is involved).
+constexpr int kPokeVecs = 224;                       // 3584 bytes per launch
+struct PokePayload { u32x4 v[kPokeVecs]; };
+}  // namespace
+
+__global__ __launch_bounds__(256) void st_poke_kernel(PokePayload p, u32x4* __restrict__ dst, int nvec) {
+  const int i = threadIdx.x;
+  if (i < nvec) dst[i] = p.v[i];
+}
+
+__global__ __launch_bounds__(256) void st_zero_kernel(u32x4* __restrict__ dst, int64_t nvec) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * blockDim.x) dst[i] = z;
+}
+
+int noalloc_scratch(void** out_ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(::scratch));     // this device's copy of the array (the current device's)
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out_ptr = g_scratch_ptr[dev];
+  return 0;
+}
+
+int launch_poke(const void* host_src, int64_t bytes, void* dst_dev, void* stream) {
+  const char* src = (const char*)host_src;
+  char* dst = (char*)dst_dev;
+  PokePayload p;
+  for (int64_t done = 0; done < bytes; done += (int64_t)sizeof(PokePayload)) {
+    const int64_t n = bytes - done < (int64_t)sizeof(PokePayload) ? bytes - done : (int64_t)sizeof(PokePayload);
+    std::memset(&p, 0, sizeof(p));
+    std::memcpy(&p, src + done, (size_t)n);
+    hipLaunchKernelGGL(st_poke_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, p, (u32x4*)(dst + done), (int)((n + 15) / 16));
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
+}
+
+int launch_zero(void* dst_dev, int64_t bytes, void* stream) {
+  const int64_t nvec = (bytes + 15) / 16;
+  if (nvec <= 0) return 0;
+  const unsigned blocks = (unsigned)((nvec + 255) / 256 < 1024 ? (nvec + 255) / 256 : 1024);
+  hipLaunchKernelGGL(st_zero_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (u32x4*)dst_dev, nvec);
   return (int)hipGetLastError();
 }
 

@@ -48,6 +48,7 @@ struct st_plan {
   std::vector<st_work_item> items_tenant;   // tenant-major, sliced by the baselines
   bool host_only = false;
   int64_t flops = 0, bytes = 0, workspace_bytes = 0;
+  int64_t ws_floats = 0, n_counters = 0;    // split-K: fp32 elements of all partial tiles, arrival counters
   // device
   TenantDev* d_tenants = nullptr;
   st_work_item* d_items_fused = nullptr;
@@ -369,6 +370,8 @@ static st_status upload(st_plan* p) {
     }
   }
   p->workspace_bytes = (int64_t)(ws_floats * 4 + counters * 4);
+  p->ws_floats = (int64_t)ws_floats;
+  p->n_counters = (int64_t)counters;
   if (p->host_only) return ST_OK;
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
   const size_t ib = p->items_fused.size() * sizeof(st_work_item);
@@ -629,6 +632,55 @@ extern "C" st_status st_conv_run(const st_plan* plan, void* hip_stream) {
   if (s != ST_OK) return s;
   if (plan->items_fused.empty()) return ST_OK;
   ST_HIP((hipError_t)launch_conv(plan->d_tenants, plan->d_items_fused, (int64_t)plan->items_fused.size(), hip_stream, nullptr));
+  return ST_OK;
+}
+
+// The fused launch for callers that cannot allocate device memory.  Scratch layout: [tenant table][work list]
+// [split-K counters][split-K partial tiles], each part on a 256-byte boundary.
+extern "C" int64_t st_conv_noalloc_max_bytes(void) { return kNoallocScratchBytes; }
+
+extern "C" st_status st_conv_run_noalloc(const st_plan* plan, void* hip_stream) {
+  if (!plan) return fail(ST_ERR_INVALID_ARG, "plan is NULL");
+  const size_t n = plan->tenants.size();
+  if (n == 0 || plan->items_fused.empty()) return ST_OK;
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  const size_t ib = plan->items_fused.size() * sizeof(st_work_item);
+  const size_t off_items = up(n * sizeof(TenantDev));
+  const size_t off_counters = off_items + up(ib);
+  const size_t off_ws = off_counters + up((size_t)plan->n_counters * 4);
+  const size_t total = off_ws + (size_t)plan->ws_floats * 4;
+  if ((int64_t)total > kNoallocScratchBytes)
+    return fail(ST_ERR_UNSUPPORTED, "st_conv_run_noalloc: the plan needs %lld bytes of tables and split-K workspace, the fixed scratch "
+                "array holds %lld", (long long)total, (long long)kNoallocScratchBytes);
+  void* base = nullptr;
+  ST_HIP((hipError_t)noalloc_scratch(&base));
+  char* dev = (char*)base;
+  std::vector<char> host;
+  try {
+    host.assign(off_counters, 0);
+  } catch (const std::bad_alloc&) {
+    return fail(ST_ERR_OUT_OF_MEMORY, "host allocation failed");
+  }
+  TenantDev* table = (TenantDev*)host.data();
+  std::memcpy(table, plan->tenants.data(), n * sizeof(TenantDev));
+  size_t wf = 0, ct = 0;
+  for (size_t t = 0; t < n; ++t) {
+    const st_tenant_info& ti = plan->info[t];
+    table[t].ws = nullptr;
+    table[t].counters = nullptr;
+    if (ti.split_k > 1) {
+      table[t].ws = (float*)(dev + off_ws) + wf;
+      table[t].counters = (uint32_t*)(dev + off_counters) + ct;
+      wf += (size_t)ti.tiles_m * ti.tiles_n * ti.split_k * ti.MT * ti.NT;
+      ct += (size_t)ti.tiles_m * ti.tiles_n;
+    }
+  }
+  std::memcpy(host.data() + off_items, plan->items_fused.data(), ib);
+  ST_HIP((hipError_t)launch_poke(host.data(), (int64_t)off_counters, dev, hip_stream));
+  // the array keeps the last call's contents: the arrival counters must start at zero (the partial tiles need not)
+  if (plan->n_counters > 0) ST_HIP((hipError_t)launch_zero(dev + off_counters, (int64_t)up((size_t)plan->n_counters * 4), hip_stream));
+  ST_HIP((hipError_t)launch_conv((const TenantDev*)dev, (const st_work_item*)(dev + off_items), (int64_t)plan->items_fused.size(),
+                                 hip_stream, nullptr));
   return ST_OK;
 }
 

@@ -18,7 +18,7 @@ ST_LAYOUT_NHWC_KRSC, ST_LAYOUT_NCHW_KCRS = 0, 1
 ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
-EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
+EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_noalloc", "st_conv_noalloc_max_bytes", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_run_plans_on_streams_many", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
@@ -93,6 +93,10 @@ def lib() -> ctypes.CDLL:
         L.st_conv_plan.argtypes = [P(st_conv_desc), i32, P(st_plan_opts), P(vp)]
         L.st_conv_run.argtypes = [vp, vp]
         L.st_conv_run_time_only.argtypes = [vp, vp]
+        L.st_conv_run_noalloc.argtypes = [vp, vp]
+        L.st_conv_run_noalloc.restype = i32
+        L.st_conv_noalloc_max_bytes.argtypes = []
+        L.st_conv_noalloc_max_bytes.restype = i64
         L.st_conv_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_conv_run_space_only.argtypes = [vp, P(vp), i32]
         L.st_conv_run_tenant_times.argtypes = [vp, vp, P(i64), P(i64), i32]
@@ -231,6 +235,14 @@ def _check(st, where):
 
 def st_conv_run(plan: Plan, stream=None) -> None:
     _check(lib().st_conv_run(plan.handle, _stream(stream)), "st_conv_run")
+
+
+def st_conv_run_noalloc(plan: Plan, stream=None) -> None:
+    _check(lib().st_conv_run_noalloc(plan.handle, _stream(stream)), "st_conv_run_noalloc")
+
+
+def st_conv_noalloc_max_bytes() -> int:
+    return int(lib().st_conv_noalloc_max_bytes())
 
 
 def st_conv_run_profiled(plan: Plan, stream=None) -> np.ndarray:
