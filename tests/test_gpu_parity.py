@@ -151,21 +151,50 @@ def test_fused_equals_solo_bitwise_and_distinct_weights(torch):
 
 
 def test_split_k_is_deterministic(torch):
+    """The split-K hand-off crosses XCDs (partial tiles written by one workgroup, summed by another).  More than a
+    thousand launches, rotating through three copies of the tensors (so operands and workspaces are not simply cache
+    resident from the launch before) and two plans with different split factors; every output is compared bit for
+    bit with the first launch of its plan, stopping at the first mismatch."""
     from tests import helpers
-    tenants = helpers.make_tenants(2)
-    plan = helpers.plan_for(tenants, split_k=6)
+    copies = [helpers.make_tenants(2) for _ in range(3)]
+    plans = {split: [helpers.plan_for(c, split_k=split) for c in copies] for split in (6, 4)}
+    first = {}
+    for split, ps in plans.items():
+        sc.st_conv_run(ps[0])
+        _sync(torch)
+        first[split] = [t.dy.clone() for t in copies[0]]
+        for i, t in enumerate(copies[0]):
+            helpers.check_tenant(t, f"split-K {split} tenant {i}")
+    launches = 0
+    for rnd in range(44):
+        for split, ps in plans.items():
+            # a burst of back-to-back launches on rotating copies, then one check per copy
+            for c in copies:
+                for t in c:
+                    t.clear()
+            for rep in range(4):
+                for p in ps:
+                    sc.st_conv_run(p)
+                    launches += 1
+            _sync(torch)
+            for ci, c in enumerate(copies):
+                for i, t in enumerate(c):
+                    assert torch.equal(t.dy, first[split][i]), f"round {rnd} split {split} copy {ci} tenant {i}: output changed"
+    assert launches >= 1000
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4])
+@pytest.mark.parametrize("target_items", [128, 256])
+def test_configs_planned_for_a_share_of_the_gpu(torch, cfg, target_items):
+    """The plans that the forms with several batches in flight use (the planner fills 128 or 256 workgroup slots
+    instead of the whole chip): full-size configurations, every element against the oracle."""
+    from tests import helpers
+    tenants = helpers.make_tenants(cfg)
+    plan = helpers.plan_for(tenants, target_items=target_items)
     sc.st_conv_run(plan)
     _sync(torch)
-    first = [t.dy.clone() for t in tenants]
-    for _ in range(25):
-        for t in tenants:
-            t.clear()
-        sc.st_conv_run(plan)
-        _sync(torch)
-        for i, t in enumerate(tenants):
-            assert torch.equal(t.dy, first[i])
-    for i, t in enumerate(tenants):
-        helpers.check_tenant(t, f"split-K tenant {i}")
+    worst = max(helpers.check_tenant(t, f"cfg{cfg} target_items={target_items} tenant {i}") for i, t in enumerate(tenants))
+    print(f"cfg{cfg} target_items={target_items}: max |gpu-oracle| = {worst:.3e}")
 
 
 def test_per_tenant_plan_baselines(torch):

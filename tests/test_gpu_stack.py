@@ -90,45 +90,67 @@ def test_stack_policies_agree_bitwise():
         assert (got - ref).abs().max() <= 0.1 * ref.abs().max()
 
 
-def test_resnet50_stack_full_size_sampled():
-    """The configuration bench.py times: 8 tenants, co-scheduled groups, seeded weights.  For every step and two
-    tenants (rotating), 96 output points drawn with a fixed seed are recomputed one by one by the oracle from the
-    exact tensors the step read, plus residual and ReLU, and compared with the bf16 output."""
+def _layerwise_full(stack, plans, tenants_of_plan=None, what=""):
+    """Teacher-forced, element by element: `plans[gi]` is launched for every layer group gi in order (tenants_of_plan:
+    the tenants a plan covers, default all); before each launch the exact tensors the group's steps will read are
+    downloaded, and after it every output element of every covered tenant is compared with the oracle's unrounded
+    layer result.  Returns the worst relative error."""
     import torch
     from oracle import oracle
-    from paper_1901_00041_amd.stack import ResNetStack
-    n_tenants = 8
-    stack = ResNetStack(n_tenants=n_tenants)
-    assert stack.n_launches == 49 and stack.flops == n_tenants * 8174272512
-    rng = np.random.default_rng(2024)
+    n_tenants = stack.n_tenants
+    tenants = list(range(n_tenants)) if tenants_of_plan is None else list(tenants_of_plan)
     worst = 0.0
     for gi, group in enumerate(stack.groups):
-        picks = {}
+        feeds = {}
         for i in group:
             st = stack.steps[i]
             s = st.shape
-            for t in ((i % n_tenants), ((i * 3 + 5) % n_tenants)):
-                idx = np.stack([rng.integers(s.N, size=96), rng.integers(s.K, size=96), rng.integers(s.P, size=96),
-                                rng.integers(s.Q, size=96)], axis=1).astype(np.int32)
-                x = _nchw(stack.view(st.src, t, s.N, s.H, s.W, s.C))
-                r = _nchw(stack.view(st.res, t, s.N, s.P, s.Q, s.K)) if st.res is not None else None
-                picks[(i, t)] = (idx, x, r)
-        stack.run_group(gi)
+            feeds[i] = ({t: _nchw(stack.view(st.src, t, s.N, s.H, s.W, s.C)) for t in tenants},
+                        {t: (_nchw(stack.view(st.res, t, s.N, s.P, s.Q, s.K)) if st.res is not None else None) for t in tenants})
+        sc.st_conv_run(plans[gi])
+        for i in group:
+            st = stack.steps[i]
+            if st.pool_after:
+                s = st.shape
+                sc.st_maxpool_nhwc(stack.buf[st.dst], stack.buf[st.pool_dst], n_tenants * s.N, s.P, s.Q, s.K, 3, 2, 1, "bf16")
         torch.cuda.synchronize()
-        for (i, t), (idx, x, r) in picks.items():
+        for i in group:
             st = stack.steps[i]
             s = st.shape
-            ref = oracle.conv2d_points(x, synth.gen_weight(5, t, st.index, s, 2.0), idx, s.stride, s.pad)
-            if r is not None:
-                ref = ref + r[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
-            if st.relu:
-                ref = np.maximum(ref, 0.0)
-            got = _nchw(stack.view(st.dst, t, s.N, s.P, s.Q, s.K))[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
-            err = np.abs(got - ref)
-            assert np.isfinite(got).all() and (err <= 1e-2 * (np.abs(ref) + 1.0)).all(), \
-                f"step {i} {st.name} tenant {t}: max err {err.max():.3e}"
-            worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
-    print(f"full-size stack, sampled: worst relative error {worst:.3e}")
+            xs, rs = feeds[i]
+            for t in tenants:
+                w = synth.gen_weight(5, t, st.index, s, 2.0)
+                ref = oracle.conv_layer(xs[t], w, s.stride, s.pad, rs[t], st.relu)
+                got = _nchw(stack.view(st.dst, t, s.N, s.P, s.Q, s.K))
+                err = np.abs(got - ref)
+                assert np.isfinite(got).all() and (err <= 1e-2 * (np.abs(ref) + 1.0)).all(), \
+                    f"{what} step {st.index} {st.name} tenant {t}: max err {err.max():.3e}"
+                worst = max(worst, float((err / (np.abs(ref) + 1.0)).max()))
+    return worst
+
+
+@pytest.mark.parametrize("target_items", [0, 256, 128])
+def test_resnet50_stack_full_size_every_element(target_items):
+    """The configuration bench.py times (8 tenants, co-scheduled groups, seeded weights), and the same stack planned for
+    the half and quarter shares of the GPU that the forms with several batches in flight use: every output element of
+    every tenant of every step, teacher-forced."""
+    from paper_1901_00041_amd.stack import ResNetStack
+    n_tenants = 8
+    stack = ResNetStack(n_tenants=n_tenants, plan_opts=sc.plan_opts(target_items=target_items) if target_items else None)
+    assert stack.n_launches == 49 and stack.flops == n_tenants * 8174272512
+    worst = _layerwise_full(stack, stack.group_plans, what=f"target_items={target_items}")
+    print(f"full-size stack, target_items={target_items}: worst relative error {worst:.3e}")
+
+
+def test_resnet50_tenant_group_plans_every_element():
+    """The plans of the two-tenant-group form (four tenants per group, each group's launches planned for half the GPU):
+    every output element, teacher-forced, group by group."""
+    from paper_1901_00041_amd.stack import ResNetStack
+    stack = ResNetStack(n_tenants=8)
+    stack.build_tenant_groups(2)
+    for g, tg in enumerate(stack.tenant_groups):
+        worst = _layerwise_full(stack, stack.tenant_group_plans[g], tenants_of_plan=tg, what=f"tenant group {g}")
+        print(f"tenant group {g}: worst relative error {worst:.3e}")
 
 
 def test_staggered_schedule_matches_lockstep_bitwise():
