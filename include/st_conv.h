@@ -77,7 +77,9 @@ typedef struct st_plan_opts {
   int32_t target_items;  /* 0 = default; else the workgroup slots the planner's cost model fills      */
   int32_t rows_per_tile; /* 0 = choose; 1, 2 or 4 forces the output rows per work item of row-tiled   */
                          /* tenants (ignored for the others)                                         */
-  int32_t reserved[2];   /* must be 0                                                                */
+  int32_t chain_queues;  /* st_chain_plan only: 0 = choose; 1 = one work queue for the whole chip; 2 = one  */
+                         /* queue per XCD, each sequence bound to one XCD (needs a whole 8-XCD device)      */
+  int32_t reserved;      /* must be 0                                                                */
 } st_plan_opts;
 
 /* One workgroup's assignment: the bit-exact object of the plan.  tile_m counts pixel tiles (MT rows
@@ -254,6 +256,82 @@ st_status st_pipeline_run(st_pipeline* pipeline, const st_plan* plan);
 st_status st_pipeline_run_many(st_pipeline* pipeline, const st_plan* const* plans, int32_t n_plans, int32_t rounds);
 st_status st_pipeline_sync(st_pipeline* pipeline);
 void st_pipeline_destroy(st_pipeline* pipeline);
+
+/* ---- A whole chain of dependent layers as ONE launch -------------------------------------------------------
+ * The space-time policy of Section 4 applied across layers as well as across tenants: the work items of every
+ * op (a convolution layer, or a max-pool) of every tenant go into one queue, and one persistent launch works
+ * through it.  Ops are grouped into SEQUENCES (one per tenant network: Section 4's disjoint graphs) and, within a
+ * sequence, ordered by STAGE: an op's work items start once every work item of its sequence's ops with a smaller
+ * stage is complete; ops of one sequence with equal stage are independent of each other (a block's projection
+ * convolution and its first 1x1 convolution, say); different sequences never wait for each other.  The caller
+ * guarantees that this order covers every read-after-write, write-after-read and write-after-write between the
+ * ops of a sequence, and that sequences share no written tensor.
+ *
+ * Tiles are chosen per stage (all ops of that stage, over all sequences, planned together as st_conv_plan would).
+ * A queue is stage-major, longest work item first within a stage.  There is either one queue for the whole chip,
+ * or (the default from 8 sequences on, on a whole 8-XCD device) one queue per XCD with sequence s in queue
+ * s mod 8, served only by the workgroups that run on that XCD: a sequence's activations then stay in one XCD's
+ * L2, and a consumer only has to drop its compute unit's vector cache instead of making the whole L2 coherent.
+ * Workgroups claim entries in queue order, so the launch needs no co-residency guarantee; every dependency wait
+ * is bounded by a wall-clock limit (default 100 ms) and a poll count, after which the launch abandons the pass:
+ * every workgroup leaves, outputs are incomplete, and st_chain_aborted reports it.  Same ops + same inputs => outputs bitwise identical from run to run, and bitwise
+ * identical to running the stages one st_conv_run at a time with the same tiles. */
+typedef enum { ST_OP_CONV = 0, ST_OP_MAXPOOL = 1 } st_op_kind;
+
+typedef struct st_chain_op {
+  int32_t kind;       /* st_op_kind                                                                       */
+  int32_t sequence;   /* 0 <= sequence < 4096                                                             */
+  int32_t stage;      /* >= 0; see above                                                                  */
+  int32_t reserved;   /* must be 0                                                                        */
+  st_conv_desc conv;  /* ST_OP_CONV: the layer.  ST_OP_MAXPOOL: N, C, H, W, R = S = window, stride, pad,  */
+                      /* in_dtype = out_dtype, x (N*H*W*C) and y (N*P*Q*C) are used, K must equal C, and   */
+                      /* C must be a multiple of the 16-byte vector (8 for 16-bit types, 4 for fp32);     */
+                      /* padding never wins the maximum                                                   */
+} st_chain_op;
+
+typedef struct st_chain_info {
+  int32_t n_ops, n_sequences, n_stages;
+  int32_t workgroups;        /* size of the persistent launch (resident workgroup slots, or fewer)    */
+  int64_t n_items;           /* queue entries                                                         */
+  int64_t flops, bytes;      /* sums over the convolution ops (as st_plan_info)                       */
+  int64_t workspace_bytes;   /* split-K partial tiles and counters (shared by a sequence's stages)    */
+  int32_t host_only;
+  int32_t n_queues;          /* 1, or 8: one queue per XCD                                            */
+  int64_t queue_begin[9];    /* queue q is entries [queue_begin[q], queue_begin[q+1]) of the work list */
+} st_chain_info;
+
+typedef struct st_chain_op_info {
+  int32_t sequence, stage, kind;
+  uint32_t need;             /* work items of its sequence that must be complete before this op starts */
+  int64_t item_count;        /* its work items                                                         */
+  st_tenant_info tile;       /* convolution ops: sizes and the planner's choice (item_begin unused)    */
+} st_chain_op_info;
+
+typedef struct st_chain st_chain; /* opaque */
+
+/* Validates the ops (as st_conv_plan does; ST_ERR_UNSUPPORTED for a max-pool whose channel count is not a
+ * multiple of the vector), plans every stage, builds the queue, allocates and uploads one device arena (tables,
+ * queue, control blocks, split-K workspace) unless opts->host_only.  n_ops == 0 gives an empty chain.  opts as for
+ * st_conv_plan (order is ignored: the queue order is fixed). */
+st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const st_plan_opts* opts, st_chain** out_chain);
+/* One pass: one launch on hip_stream.  Asynchronous, allocation-free.  Two runs of one chain must not overlap in
+ * time (queue them on one stream). */
+st_status st_chain_run(st_chain* chain, void* hip_stream);
+/* The same with in-kernel time stamps per queue entry (HOST buffer of 8 uint64 per entry, as st_conv_run_profiled;
+ * slot [7] = ticks of the 100 MHz clock the entry waited for its dependency).  Synchronous diagnostic. */
+st_status st_chain_run_profiled(st_chain* chain, void* hip_stream, uint64_t* stamps, int64_t capacity);
+/* Waits for the device, then *aborted = 1 if any run since the last call gave up on a dependency wait, or if the
+ * last run did not complete every work item (an XCD that received no workgroups); the chain is reset. */
+st_status st_chain_aborted(st_chain* chain, int32_t* aborted);
+/* The wall-clock limit of a dependency wait in microseconds (0 = give up at once unless already satisfied: a test
+ * hook that makes every kernel still exit normally). */
+st_status st_chain_set_wait_limit_us(st_chain* chain, int64_t microseconds);
+st_status st_chain_get_info(const st_chain* chain, st_chain_info* out);
+st_status st_chain_get_op_info(const st_chain* chain, int32_t op, st_chain_op_info* out);
+/* Host copy of the queue, valid until the chain is destroyed; st_work_item.tenant is the op's index in the ops
+ * array given to st_chain_plan. */
+st_status st_chain_worklist(const st_chain* chain, const st_work_item** items, int64_t* n_items);
+void st_chain_destroy(st_chain* chain);
 
 /* Introspection (used by the bit-exact work-list tests and by reports). */
 st_status st_conv_plan_info(const st_plan* plan, st_plan_info* out);

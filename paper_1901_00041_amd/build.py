@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJDIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libst_conv.so")
-SOURCES = ["st_kernels.hip", "st_plan.cpp"]
+SOURCES = ["st_kernels.hip", "st_chain.hip", "st_plan.cpp", "st_chain.cpp"]
 # the benchmark's achievable-roof probe: its own small library, not part of the convolution library's ABI
 PROBE_LIB = os.path.join(PKG, "libst_bench_probe.so")
 PROBE_SOURCES = ["st_bench_probe.hip"]
@@ -39,7 +39,7 @@ def _run(cmd, verbose):
 
 
 def _headers_mtime() -> float:
-    hs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    hs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     return max(os.path.getmtime(h) for h in hs)
 
 

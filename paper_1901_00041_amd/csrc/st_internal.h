@@ -21,6 +21,7 @@ struct TileShape {
 constexpr int kNumTileCfgs = 7;
 constexpr int kRowCfg = 6;         // the row tile for few-channel layers (conv_tile_rows): 128-pixel segments of
                                    // kRowsPerTile consecutive output rows x 64 filters, one filter row per K step
+constexpr int kChainPoolCfg = 7;   // chain kernel only: TenantDev.cfg of a max-pool op (not a convolution tile shape)
 constexpr int kRowsPerTile = 4;    // most output rows one row-tile work item may take (the planner picks 1, 2 or 4)
 constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {128, 128, 2, 2, 32, 128, 2},  // 0: wave tile 64x64
@@ -64,12 +65,29 @@ struct TenantDev {
   int32_t rows_per_tile;      // row tile only: output rows per work item
   int32_t row_pitch;          // row tile only: bytes of one image row in LDS (padding included, multiple of 16)
   int32_t k_across_waves;     // 1: each wavefront computes the whole tile over a quarter of every K step
+  // chain kernel only (st_chain.hip); the per-plan kernel ignores them
+  int32_t chain_seq;          // sequence whose completion counter this op's work items wait on and bump
+  uint32_t chain_need;        // work items of that sequence that must be complete before this op's may start
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 
 // Launchers implemented in st_kernels.hip.  All asynchronous; return the hipError_t as int.
 int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int64_t n_items, void* stream,
                 uint64_t* prof_dev);
+// Persistent chain launch (st_chain.hip).  ctl / ctl_other: this run's and the next run's control block.  A block is
+// ctl_slots slots of kChainCtlStride 32-bit words (256 bytes) with one live word each, so that the words hundreds of
+// workgroups poll and bump sit in different cache lines and memory channels: slot kChainCtlAbort the abort flag,
+// kChainCtlDone the count of completed work items, kChainCtlHead + q the head of queue q, kChainCtlSeq + s the
+// completion counter of sequence s.  qbegin: n_queues + 1 queue boundaries (host array).
+constexpr int kChainCtlStride = 64;
+constexpr int kChainCtlAbort = 1, kChainCtlDone = 2, kChainCtlHead = 4, kChainCtlSeq = 16;
+constexpr uint32_t kChainFlagReleaseFence = 1u;   // device-scope release fence before every completion
+constexpr uint32_t kChainFlagAcquireAgent = 2u;   // device-scope acquire after a dependency wait
+constexpr uint32_t kChainFlagAcquireL1 = 4u;      // invalidate only the compute unit's vector cache after a wait
+int chain_max_workgroups(int* out_workgroups, int* out_xcds);
+int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const uint32_t* qbegin, uint32_t n_queues, uint32_t* ctl,
+                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t spin_limit_ticks, uint32_t flags, int grid, void* stream,
+                 uint64_t* prof_dev);
 int launch_empty(void* stream);
 // Allocation-free path: device address of the current GPU's fixed scratch array (looked up on first use per device),
 // host bytes -> device through kernel arguments (sizes rounded up to 16 bytes; dst 16-byte aligned), and a zero fill.

@@ -12,6 +12,7 @@
 #include <thread>
 #include <vector>
 
+#include "st_host.h"
 #include "st_internal.h"
 
 using namespace st;
@@ -21,52 +22,16 @@ using namespace st;
 // ---------------------------------------------------------------------------------------------------
 static thread_local char g_err[512] = "";
 
-static st_status fail(st_status s, const char* fmt, ...) {
+st_status st::fail(st_status s, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
   return s;
 }
-static st_status hip_fail(hipError_t e, const char* what) {
+st_status st::hip_fail(hipError_t e, const char* what) {
   return fail(e == hipErrorOutOfMemory ? ST_ERR_OUT_OF_MEMORY : ST_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
-#define ST_HIP(call)                                   \
-  do {                                                 \
-    hipError_t e_ = (call);                            \
-    if (e_ != hipSuccess) return hip_fail(e_, #call);  \
-  } while (0)
-
-// ---------------------------------------------------------------------------------------------------
-// plan object
-// ---------------------------------------------------------------------------------------------------
-struct st_plan {
-  std::vector<st_conv_desc> descs;
-  std::vector<st_tenant_info> info;
-  std::vector<TenantDev> tenants;           // host mirror of the device table
-  std::vector<st_work_item> items_fused;    // order of the fused launch
-  std::vector<st_work_item> items_tenant;   // tenant-major, sliced by the baselines
-  bool host_only = false;
-  int64_t flops = 0, bytes = 0, workspace_bytes = 0;
-  int64_t ws_floats = 0, n_counters = 0;    // split-K: fp32 elements of all partial tiles, arrival counters
-  // device
-  TenantDev* d_tenants = nullptr;
-  st_work_item* d_items_fused = nullptr;
-  st_work_item* d_items_tenant = nullptr;
-  char* d_arena = nullptr;                  // the one device allocation the four pointers below point into
-  char* d_workspace = nullptr;              // split-K counters, then all tenants' partial tiles
-  hipEvent_t ev_fork = nullptr;
-  std::vector<hipEvent_t> ev_join;          // one per stream slot used by space-only
-  // pinned staging slots for stream-ordered uploads of the tenant table (st_conv_plan_rebind_all)
-  static constexpr int kStageSlots = 4;
-  TenantDev* h_stage[kStageSlots] = {nullptr, nullptr, nullptr, nullptr};
-  hipEvent_t ev_stage[kStageSlots] = {nullptr, nullptr, nullptr, nullptr};
-  bool stage_used[kStageSlots] = {false, false, false, false};
-  int stage_next = 0;
-};
-
-
-static int elem_size(int dt) { return dt == ST_DT_F32 ? 4 : 2; }
 
 static st_status validate(const st_conv_desc& d, int t) {
   if (d.N <= 0 || d.C <= 0 || d.H <= 0 || d.W <= 0 || d.K <= 0 || d.R <= 0 || d.S <= 0)
@@ -99,7 +64,6 @@ static st_status validate(const st_conv_desc& d, int t) {
   return ST_OK;
 }
 
-static int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // Multiplier and shift with floor(n/d) == ((n*m) >> 31) >> L for every 0 <= n < 2^31 and 1 <= d < 2^31
 // (m = floor(2^(31+L)/d) + 1 fits 32 bits because d > 2^(L-1); m*d - 2^(31+L) <= d, so the error of n*m/2^(31+L)
@@ -431,7 +395,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
   if (o.tile_cfg < 0 || o.tile_cfg > kNumTileCfgs) return fail(ST_ERR_INVALID_ARG, "opts.tile_cfg out of range");
   if (o.split_k < 0 || o.order < 0 || o.order > 2 || o.target_items < 0 ||
       !(o.rows_per_tile == 0 || o.rows_per_tile == 1 || o.rows_per_tile == 2 || o.rows_per_tile == 4) ||
-      o.reserved[0] != 0 || o.reserved[1] != 0)
+      o.chain_queues < 0 || o.chain_queues > 2 || o.reserved != 0)
     return fail(ST_ERR_INVALID_ARG, "opts: negative or unknown value");
   for (int t = 0; t < n_tenants; ++t) {
     st_status s = validate(descs[t], t);

@@ -28,6 +28,16 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 
+// The thread's index in its workgroup, read afresh wherever a work item starts.  Inside a loop over work items the
+// compiler would otherwise compute everything that depends only on the thread index (lane geometry, staging rows of
+// every tile shape) once before the loop and keep it alive in registers through all of it.
+__device__ __forceinline__ int work_thread_id() {
+  int t = (int)threadIdx.x;
+  asm volatile("" : "+v"(t));
+  __builtin_assume(t >= 0 && t < kThreads);
+  return t;
+}
+
 template <int DT> struct ElemOf;
 template <> struct ElemOf<ST_DT_F32> { static constexpr int ES = 4; };
 template <> struct ElemOf<ST_DT_BF16> { static constexpr int ES = 2; };
@@ -154,8 +164,8 @@ constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every bu
 // im2col row m0 and first filter n0; rows at or past m_end are not stored.
 // The transposition buffer `smem` holds MT/PASSES pixel rows; with PASSES > 1 the tile is written out in
 // that many slices of consecutive pixel rows.
-template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, int CAP = kSmemBytes, class Acc>
-__device__ __forceinline__ void tile_epilogue(const TenantDev& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
+template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, int CAP = kSmemBytes, class Acc, class TD>
+__device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
                                               int wn0, int lrow, int lk, int tid, char* smem, uint64_t* prof = nullptr) {
   constexpr int NG = (MF == 32) ? 4 : 1;
   const bool relu = (T.epilogue & ST_EPI_RELU) != 0u;
@@ -413,8 +423,8 @@ _Pragma("unroll")
 // quarter of each K step (sub-step = wavefront index), so every staged byte is read from LDS exactly once.  After
 // the K loop the four partial tiles are summed through LDS, in wavefront order, into the accumulators the
 // pixel/filter division would have produced, and everything downstream (split-K, epilogue) is unchanged.
-template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false>
-__device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false, class TD>
+__device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int ES = ElemOf<DT>::ES;
   constexpr int VEC = 16 / ES;          // elements per 16-byte vector
   constexpr int KT = KB / ES;           // elements of K per step
@@ -438,7 +448,7 @@ __device__ __forceinline__ void conv_tile(const TenantDev& T, const st_work_item
   char* sA = smem;                          // [2][MT][ROWB]  patches
   char* sB = smem + 2 * MT * ROWB;          // [2][NT][ROWB]  filters
 
-  const int tid = threadIdx.x;
+  const int tid = work_thread_id();
   if (prof && tid == 0) {
     prof[0] = __builtin_readcyclecounter();
     prof[4] = wall_clock64();
@@ -791,8 +801,8 @@ __device__ __forceinline__ u32x4 window128(const u32x4& lo, const u32x4& hi, int
 // 64 filters are copied once into an LDS array [filter][r][32] padded with zeros, and the MFMA operands
 // are assembled from LDS.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by the planner:
 // 16-bit types, 8 <= S*C <= 32, W*C*2 a multiple of 16, stride*C even, LDS footprint.
-template <int DT>
-__device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+template <int DT, class TD>
+__device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
   const int RT = T.rows_per_tile;                    // output rows per work item (1..kRowsPerTile)
   constexpr int EPI_PASSES = 2;
@@ -801,7 +811,7 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   static_assert(kStageBytes >= (MT / EPI_PASSES) * (NT + 4) * 4 && kStageBytes >= MT * (NT * 2 + 16), "row tile stage buffer");
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
-  const int tid = threadIdx.x;
+  const int tid = work_thread_id();
   if (prof && tid == 0) {
     prof[0] = __builtin_readcyclecounter();
     prof[4] = wall_clock64();
@@ -986,14 +996,16 @@ __device__ __forceinline__ void conv_tile_rows(const TenantDev& T, const st_work
   }
 }
 
-template <int CFG, int DT, bool GENERIC, bool KW = false>
-__device__ __forceinline__ void run_cfg(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+template <int CFG, int DT, bool GENERIC, bool KW = false, class TD>
+__device__ __forceinline__ void run_cfg(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr TileShape s = kTileShapes[CFG];
   conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW>(T, it, smem, prof);
 }
 
-template <int DT>
-__device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item it, char* smem, uint64_t* prof) {
+// TD is TenantDev, or TenantDev qualified with the constant address space (records that no launch in flight
+// modifies: every field read is then a scalar load, however many stores, atomics and barriers surround it).
+template <int DT, class TD>
+__device__ __forceinline__ void run_dtype(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   if (T.vec_ok) {
     switch (T.cfg) {
       case 0: run_cfg<0, DT, false>(T, it, smem, prof); break;
@@ -1020,6 +1032,52 @@ __device__ __forceinline__ void run_dtype(const TenantDev& T, const st_work_item
     if (T.cfg == 1) run_cfg<1, DT, true>(T, it, smem, prof);
     else run_cfg<3, DT, true>(T, it, smem, prof);
   }
+}
+
+// ---- max-pool of one output vector (chain kernel) ---------------------------------------------------
+// NHWC max-pool, one 16-byte vector of channels of one output pixel: idx counts (n, p, q, channel vector) with the
+// channel vector fastest.  Padding never wins; the result is a copy of the winning input's bits.
+template <int DT>
+__device__ __forceinline__ u32x4 maxpool_vector(const void* __restrict__ xv, int64_t idx, int H, int W, int C, int P, int Q,
+                                                int win, int stride, int pad) {
+  constexpr int ES = ElemOf<DT>::ES, VEC = 16 / ES;
+  const int CV = C / VEC;
+  const int cv = (int)(idx % CV);
+  int64_t t = idx / CV;
+  const int q = (int)(t % Q);
+  t /= Q;
+  const int p = (int)(t % P);
+  const int n = (int)(t / P);
+  float best[VEC];
+  uint32_t bits[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { best[e] = 0.f; bits[e] = 0u; }
+  bool any = false;
+  for (int r = 0; r < win; ++r) {
+    const int h = p * stride - pad + r;
+    if ((unsigned)h >= (unsigned)H) continue;
+    for (int s = 0; s < win; ++s) {
+      const int w = q * stride - pad + s;
+      if ((unsigned)w >= (unsigned)W) continue;
+      const u32x4 raw = *(const u32x4*)((const char*)xv + ((((int64_t)n * H + h) * W + w) * C + (int64_t)cv * VEC) * ES);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        uint32_t b;
+        float v;
+        if constexpr (ES == 4) {
+          b = raw[e];
+          v = __builtin_bit_cast(float, b);
+        } else {
+          b = (raw[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+          v = (DT == ST_DT_BF16) ? bf16_bits_to_f32((uint16_t)b) : f16_bits_to_f32((uint16_t)b);
+        }
+        if (!any || v > best[e]) { best[e] = v; bits[e] = b; }
+      }
+      any = true;
+    }
+  }
+  if constexpr (ES == 4) return u32x4{bits[0], bits[1], bits[2], bits[3]};
+  else return u32x4{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
 }
 
 }  // namespace st

@@ -16,13 +16,15 @@ ST_OK, ST_ERR_INVALID_ARG, ST_ERR_UNSUPPORTED, ST_ERR_OUT_OF_MEMORY, ST_ERR_DEVI
 ST_DT_F32, ST_DT_BF16, ST_DT_F16 = 0, 1, 2
 ST_LAYOUT_NHWC_KRSC, ST_LAYOUT_NCHW_KCRS = 0, 1
 ST_EPI_RELU, ST_EPI_RESIDUAL = 1, 2
+ST_OP_CONV, ST_OP_MAXPOOL = 0, 1
 DTYPE_CODE = {"f32": ST_DT_F32, "bf16": ST_DT_BF16, "f16": ST_DT_F16}
 
 EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_noalloc", "st_conv_noalloc_max_bytes", "st_conv_run_profiled", "st_conv_run_tenant_times", "st_conv_run_time_only", "st_conv_run_space_only",
            "st_conv_run_plans_time_only", "st_conv_run_plans_space_only", "st_conv_run_plans_on_streams", "st_conv_run_plans_on_streams_many", "st_conv_plan_rebind", "st_conv_plan_rebind_all",
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
-           "st_conv_plan_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
+           "st_conv_plan_destroy", "st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
+           "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
 
@@ -36,8 +38,7 @@ class st_conv_desc(ctypes.Structure):
 
 class st_plan_opts(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("tile_cfg", "split_k", "order", "host_only", "target_items",
-                                                 "rows_per_tile")] + \
-               [("reserved", ctypes.c_int32 * 2)]
+                                                 "rows_per_tile", "chain_queues", "reserved")]
 
 
 class st_work_item(ctypes.Structure):
@@ -63,6 +64,23 @@ class st_tenant_info(ctypes.Structure):
 class st_plan_info(ctypes.Structure):
     _fields_ = [("n_tenants", ctypes.c_int32), ("host_only", ctypes.c_int32), ("n_items", ctypes.c_int64),
                 ("flops", ctypes.c_int64), ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
+
+
+class st_chain_op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("sequence", ctypes.c_int32), ("stage", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("conv", st_conv_desc)]
+
+
+class st_chain_info(ctypes.Structure):
+    _fields_ = [("n_ops", ctypes.c_int32), ("n_sequences", ctypes.c_int32), ("n_stages", ctypes.c_int32),
+                ("workgroups", ctypes.c_int32), ("n_items", ctypes.c_int64), ("flops", ctypes.c_int64),
+                ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64), ("host_only", ctypes.c_int32),
+                ("n_queues", ctypes.c_int32), ("queue_begin", ctypes.c_int64 * 9)]
+
+
+class st_chain_op_info(ctypes.Structure):
+    _fields_ = [("sequence", ctypes.c_int32), ("stage", ctypes.c_int32), ("kind", ctypes.c_int32), ("need", ctypes.c_uint32),
+                ("item_count", ctypes.c_int64), ("tile", st_tenant_info)]
 
 
 class st_plan_cache_stats(ctypes.Structure):
@@ -133,6 +151,19 @@ def lib() -> ctypes.CDLL:
         L.st_conv_plan_worklist.argtypes = [vp, i32, P(P(st_work_item)), P(i64)]
         L.st_conv_plan_destroy.argtypes = [vp]
         L.st_conv_plan_destroy.restype = None
+        L.st_chain_plan.argtypes = [P(st_chain_op), i32, P(st_plan_opts), P(vp)]
+        L.st_chain_run.argtypes = [vp, vp]
+        L.st_chain_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
+        L.st_chain_aborted.argtypes = [vp, P(i32)]
+        L.st_chain_set_wait_limit_us.argtypes = [vp, i64]
+        L.st_chain_get_info.argtypes = [vp, P(st_chain_info)]
+        L.st_chain_get_op_info.argtypes = [vp, i32, P(st_chain_op_info)]
+        L.st_chain_worklist.argtypes = [vp, P(P(st_work_item)), P(i64)]
+        L.st_chain_destroy.argtypes = [vp]
+        L.st_chain_destroy.restype = None
+        for name in ("st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
+                     "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist"):
+            getattr(L, name).restype = i32
         L.st_tile_shape.argtypes = [i32, P(i32), P(i32), P(i32)]
         L.st_tile_count.argtypes = []
         L.st_maxpool_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
@@ -221,10 +252,10 @@ def st_conv_plan(descs: Sequence[st_conv_desc], opts: Optional[st_plan_opts] = N
     return Plan(out.value, keep)
 
 
-def plan_opts(tile_cfg=0, split_k=0, order=0, host_only=0, target_items=0, rows_per_tile=0) -> st_plan_opts:
+def plan_opts(tile_cfg=0, split_k=0, order=0, host_only=0, target_items=0, rows_per_tile=0, chain_queues=0) -> st_plan_opts:
     o = st_plan_opts()
     o.tile_cfg, o.split_k, o.order, o.host_only, o.target_items = tile_cfg, split_k, order, host_only, target_items
-    o.rows_per_tile = rows_per_tile
+    o.rows_per_tile, o.chain_queues = rows_per_tile, chain_queues
     return o
 
 
@@ -382,6 +413,71 @@ class PlanCache:
         if getattr(self, "handle", None) and _lib is not None:
             try:
                 _lib.st_plan_cache_destroy(self.handle)
+            except Exception:      # interpreter shutdown
+                pass
+            self.handle = None
+
+    def __del__(self):
+        self.destroy()
+
+
+def make_chain_op(kind: int, sequence: int, stage: int, desc: st_conv_desc) -> st_chain_op:
+    op = st_chain_op()
+    op.kind, op.sequence, op.stage, op.reserved = kind, sequence, stage, 0
+    op.conv = desc
+    return op
+
+
+class Chain:
+    """Owns an st_chain*; keeps the tensors it borrows alive."""
+
+    def __init__(self, ops: Sequence[st_chain_op], opts: Optional[st_plan_opts] = None, keep=None):
+        n = len(ops)
+        arr = (st_chain_op * max(n, 1))(*ops)
+        out = ctypes.c_void_p()
+        _check(lib().st_chain_plan(arr, n, ctypes.byref(opts) if opts is not None else None, ctypes.byref(out)), "st_chain_plan")
+        self.handle, self._keep = out.value, keep
+
+    def run(self, stream=None) -> None:
+        _check(lib().st_chain_run(self.handle, _stream(stream)), "st_chain_run")
+
+    def run_profiled(self, stream=None) -> np.ndarray:
+        n = int(self.info().n_items)
+        out = np.zeros((max(n, 1), 8), dtype=np.uint64)
+        _check(lib().st_chain_run_profiled(self.handle, _stream(stream), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), out.size),
+               "st_chain_run_profiled")
+        return out[:n]
+
+    def aborted(self) -> bool:
+        flag = ctypes.c_int32()
+        _check(lib().st_chain_aborted(self.handle, ctypes.byref(flag)), "st_chain_aborted")
+        return bool(flag.value)
+
+    def set_wait_limit_us(self, us: int) -> None:
+        _check(lib().st_chain_set_wait_limit_us(self.handle, us), "st_chain_set_wait_limit_us")
+
+    def info(self) -> st_chain_info:
+        out = st_chain_info()
+        _check(lib().st_chain_get_info(self.handle, ctypes.byref(out)), "st_chain_get_info")
+        return out
+
+    def op_info(self, op: int) -> st_chain_op_info:
+        out = st_chain_op_info()
+        _check(lib().st_chain_get_op_info(self.handle, op, ctypes.byref(out)), "st_chain_get_op_info")
+        return out
+
+    def worklist(self) -> np.ndarray:
+        p = ctypes.POINTER(st_work_item)()
+        n = ctypes.c_int64()
+        _check(lib().st_chain_worklist(self.handle, ctypes.byref(p), ctypes.byref(n)), "st_chain_worklist")
+        if n.value == 0:
+            return np.zeros(0, dtype=WORK_ITEM_DTYPE)
+        return np.frombuffer(ctypes.string_at(p, n.value * ctypes.sizeof(st_work_item)), dtype=WORK_ITEM_DTYPE).copy()
+
+    def destroy(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            try:
+                _lib.st_chain_destroy(self.handle)
             except Exception:      # interpreter shutdown
                 pass
             self.handle = None

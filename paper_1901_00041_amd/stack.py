@@ -25,11 +25,27 @@ from . import synth
 
 class ResNetStack:
     def __init__(self, n_tenants: int = 8, cfg: int = 5, batch: int = 1, image: int = 224, seeded_weights: bool = True,
-                 plan_opts=None, co_schedule: bool = True):
+                 plan_opts=None, co_schedule: bool = True, unique_buffers: bool = False):
         import torch
         self.torch = torch
         self.n_tenants, self.cfg = n_tenants, cfg
         self.steps: List[synth.Step] = synth.resnet50_steps(batch, image)
+        if unique_buffers:
+            # every step writes a buffer of its own (nothing is overwritten within a pass), so that after ONE launch
+            # over the whole network every layer's inputs and outputs can still be read back
+            import dataclasses
+            latest, fresh, steps = {0: 0}, 100, []
+            for st in self.steps:
+                src, res = latest[st.src], (latest[st.res] if st.res is not None else None)
+                dst, fresh = fresh, fresh + 1
+                pool_dst = None
+                if st.pool_after:
+                    pool_dst, fresh = fresh, fresh + 1
+                steps.append(dataclasses.replace(st, src=src, dst=dst, res=res, pool_dst=pool_dst))
+                latest[st.dst] = dst
+                if st.pool_after:
+                    latest[st.pool_dst] = pool_dst
+            self.steps = steps
         dev = "cuda"
         # activation buffers: one tensor per buffer id holding every tenant (tenant-major), sized for the
         # largest use of that id
@@ -258,7 +274,30 @@ class ResNetStack:
             done.record(s)
             anchor.wait_event(done)
 
+    # ---- the whole pass as one persistent launch --------------------------------------------------------
+    def build_chain(self, opts=None) -> None:
+        """One chain over every tenant's whole network: tenant t is sequence t; a layer group is a stage (the
+        projection conv and the block's first 1x1 conv share one), the max-pool after the stem a stage of its own."""
+        ops = []
+        for gi, group in enumerate(self.groups):
+            for i in group:
+                st = self.steps[i]
+                s = st.shape
+                for t in range(self.n_tenants):
+                    ops.append(sc.make_chain_op(sc.ST_OP_CONV, t, 2 * gi, self._step_descs[i][t]))
+                    if st.pool_after:
+                        p = (s.P + 2 - 3) // 2 + 1
+                        d = sc.make_desc(s.N, s.K, s.P, s.Q, s.K, 3, 3, 2, 1, "bf16", "bf16", self.buf[st.dst][t], None, self.buf[st.pool_dst][t])
+                        ops.append(sc.make_chain_op(sc.ST_OP_MAXPOOL, t, 2 * gi + 1, d))
+        self.chain = sc.Chain(ops, opts if opts is not None else self._plan_opts, keep=[self.buf, self.weights])
+        self.chain_ops = ops
+
     def run(self, policy: str = "fused", stream=None) -> None:
+        if policy == "fused_chain":
+            if getattr(self, "chain", None) is None:
+                self.build_chain()
+            self.chain.run(stream)
+            return
         if policy.startswith("fused_groups"):
             n = int(policy[len("fused_groups"):])
             if getattr(self, "tenant_groups", None) is None or len(self.tenant_groups) != n:
