@@ -82,7 +82,7 @@ def test_chain_matches_layer_launches_bitwise_on_reused_buffers(chain_queues):
                 b.zero_()
 
     scrub()
-    stack.build_chain(sc.plan_opts(chain_queues=chain_queues))
+    stack.build_chain(chain_queues)
     assert stack.chain.info().n_queues == (8 if chain_queues == 0 else 1)
     for rep in range(60):
         stack.run("fused_chain")

@@ -129,11 +129,12 @@ def _layerwise_full(stack, plans, tenants_of_plan=None, what=""):
     return worst
 
 
-@pytest.mark.parametrize("target_items", [0, 256, 128])
+@pytest.mark.parametrize("target_items", [0, 400, 256, 128])
 def test_resnet50_stack_full_size_every_element(target_items):
-    """The configuration bench.py times (8 tenants, co-scheduled groups, seeded weights), and the same stack planned for
-    the half and quarter shares of the GPU that the forms with several batches in flight use: every output element of
-    every tenant of every step, teacher-forced."""
+    """The configuration bench.py times (8 tenants, co-scheduled groups, seeded weights; target_items 0 = the stack's own
+    default), the same stack with the planner's general default (400 slots), and planned for the half and quarter
+    shares of the GPU that the forms with several batches in flight use: every output element of every tenant of
+    every step, teacher-forced."""
     from paper_1901_00041_amd.stack import ResNetStack
     n_tenants = 8
     stack = ResNetStack(n_tenants=n_tenants, plan_opts=sc.plan_opts(target_items=target_items) if target_items else None)
