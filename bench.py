@@ -692,8 +692,7 @@ def measure(cfg: int, steps: int, warmup: int, policies, extras: bool, extra_ste
             out[f"speedup_vs_{base}"] = cands[best] / fused["ms_per_step"]
             out[f"{base}_form"] = best
     out["roofline"] = roofline(wl, head, fused)
-    if head != "fused" and "fused" in pol:
-        out["roofline_fused_layer_launches"] = roofline(wl, "fused", pol["fused"])
+    out["rooflines"] = {f: roofline(wl, f, pol[f]) for f in pol if f in wl.launches}
     if extras:
         ex = {}
         for form in wl.extra_forms:
@@ -728,6 +727,7 @@ def main():
     ap.add_argument("--isolation", action="store_true", help="per-tenant completion spread of identical tenants: fused launch vs space-only")
     ap.add_argument("--occupancy", action="store_true", help="per-tenant occupancy table of one fused launch of --config (1-4), as markdown")
     ap.add_argument("--probes", action="store_true", help="achievable copy bandwidth and MFMA rates of this chip")
+    ap.add_argument("--form", default="", help="with --counters: the form to run (default: the headline form of --config)")
     ap.add_argument("--counters", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: only K passes of the headline form of --config and K launches "
                          "of a 64 MiB copy kernel (the known-traffic reference); prints a short JSON line")
@@ -762,7 +762,7 @@ def main():
         return
     if args.counters:
         wl = Workload(args.config)
-        form = HEADLINE_FORM[args.config] if HEADLINE_FORM[args.config] in wl.forms else "fused"
+        form = args.form or HEADLINE_FORM[args.config]
         k = args.steps
         src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -800,8 +800,7 @@ def main():
         "roofline": head["roofline"],
         "paper_context": PAPER_CONTEXT,
     }
-    if "roofline_fused_layer_launches" in head:
-        line["roofline_fused_layer_launches"] = head["roofline_fused_layer_launches"]
+    line["rooflines"] = head["rooflines"]
     if "extras" in head:
         line["extras"] = head["extras"]
     if not args.no_extras:

@@ -107,10 +107,9 @@ typedef struct st_tenant_info {
   int64_t item_count;          /*   tenant-major work list belongs to this tenant           */
   int32_t row_tiled;           /* 1: pixel tiles are row segments of consecutive output rows */
   int32_t rows_per_tile;       /* output rows per tile when row_tiled, else 0                */
-  int32_t xcd_group_by;        /* work items kept on one XCD (launch position mod 8) share: 0 nothing, */
-                               /* 1 a weight slice (filter tile, K slice), 2 an activation slice     */
-                               /* (pixel tile, K slice)                                              */
-  int32_t reserved;
+  int32_t xcd_blocks_m;        /* XCD placement (workgroup b of a launch runs on XCD b mod 8): the tiles are */
+  int32_t xcd_blocks_n;        /* cut into xcd_blocks_m ranges of pixel tiles x xcd_blocks_n ranges of filter */
+                               /* tiles, at most 8 blocks, each kept on one XCD as far as an even spread allows */
 } st_tenant_info;
 
 typedef struct st_plan_info {

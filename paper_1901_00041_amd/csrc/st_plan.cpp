@@ -128,21 +128,24 @@ static bool row_tile_ok(const st_conv_desc& d) {
 }
 
 // XCD-aware placement.  The hardware hands workgroup b of a launch to XCD b mod 8, and each XCD has an L2 of
-// its own, so work items that read the same slice of an operand should sit at positions that are equal
-// mod 8.  Items are grouped by the operand slice whose re-reads would cost more (xcd_group_by: 1 = weights,
-// group = (filter tile, K slice), shared by the pixel tiles; 2 = activations, group = (pixel tile, K slice),
-// shared by the filter tiles); group g prefers XCD g mod 8.  The items of a run are dealt out position by
-// position: position q (XCD (phase + q) mod 8) takes the next item that prefers this XCD, or, when none is
-// left, the next item of the XCD with the most items left (lowest XCD on ties).
+// its own, so what one XCD's work items read is fetched into that L2 once, and every operand slice is fetched once
+// per XCD that has an item reading it.  A tenant's tiles are cut into xcd_blocks_m x xcd_blocks_n blocks (contiguous
+// ranges of pixel tiles x contiguous ranges of filter tiles, at most 8 blocks); block g = bm * xcd_blocks_n + bn
+// prefers XCD g, all K slices of a tile with it.  The XCDs together then fetch the activations xcd_blocks_n times and
+// the filters xcd_blocks_m times.  The items of a run are dealt out position by position: position q (XCD
+// (phase + q) mod 8) takes the next item that prefers this XCD, or, when none is left, the next item of the XCD with
+// the most items left (lowest XCD on ties).
+static int xcd_block_of(const st_work_item& it, const st_tenant_info& ti) {
+  const int64_t bm = (int64_t)it.tile_m * ti.xcd_blocks_m / ti.tiles_m;
+  const int64_t bn = (int64_t)it.tile_n * ti.xcd_blocks_n / ti.tiles_n;
+  return (int)(bm * ti.xcd_blocks_n + bn);
+}
+
 static void xcd_arrange(st_work_item* items, int64_t n, int phase, const st_tenant_info& ti) {
-  if (ti.xcd_group_by == 0 || n < 2) return;
+  if (ti.xcd_blocks_m * ti.xcd_blocks_n <= 1 || n < 2) return;
   std::vector<st_work_item> bucket[kNumXCDs];
   size_t head[kNumXCDs] = {};
-  for (int64_t i = 0; i < n; ++i) {
-    const st_work_item& it = items[i];
-    const int64_t g = (int64_t)(ti.xcd_group_by == 1 ? it.tile_n : it.tile_m) * ti.split_k + it.k_split_idx;
-    bucket[g % kNumXCDs].push_back(it);
-  }
+  for (int64_t i = 0; i < n; ++i) bucket[xcd_block_of(items[i], ti) % kNumXCDs].push_back(items[i]);
   for (int64_t q = 0; q < n; ++q) {
     int x = (int)((phase + q) % kNumXCDs);
     if (head[x] == bucket[x].size()) {
@@ -154,13 +157,24 @@ static void xcd_arrange(st_work_item* items, int64_t n, int phase, const st_tena
   }
 }
 
-static int xcd_group_choice(const st_conv_desc& d, const st_tenant_info& ti) {
+// The block grid of a tenant: among the grids a x b with a, b in {1, 2, 4, 8}, a * b <= 8, a <= tiles_m, b <= tiles_n,
+// the one with the most blocks, then the fewest bytes fetched over all XCDs (b times the activations plus a times the
+// filters), then the smallest a.
+static void xcd_block_choice(const st_conv_desc& d, st_tenant_info* ti) {
   const int64_t es = elem_size(d.in_dtype);
-  const int64_t w_bytes = ti.Ngemm * ti.Kgemm * es, x_bytes = (int64_t)d.N * d.C * d.H * d.W * es;
-  const int64_t save_w = (std::min<int64_t>(ti.tiles_m, kNumXCDs) - 1) * w_bytes;
-  const int64_t save_x = (std::min<int64_t>(ti.tiles_n, kNumXCDs) - 1) * x_bytes;
-  if (save_w <= 0 && save_x <= 0) return 0;
-  return save_w >= save_x ? 1 : 2;
+  const int64_t w_bytes = ti->Ngemm * ti->Kgemm * es, x_bytes = (int64_t)d.N * d.C * d.H * d.W * es;
+  int best_a = 1, best_b = 1;
+  int64_t best_cost = x_bytes + w_bytes;
+  for (int a = 1; a <= kNumXCDs; a *= 2)
+    for (int b = 1; a * b <= kNumXCDs; b *= 2) {
+      if (a > ti->tiles_m || b > ti->tiles_n) continue;
+      const int64_t cost = b * x_bytes + a * w_bytes;
+      if (a * b > best_a * best_b || (a * b == best_a * best_b && cost < best_cost)) {
+        best_a = a; best_b = b; best_cost = cost;
+      }
+    }
+  ti->xcd_blocks_m = best_a;
+  ti->xcd_blocks_n = best_b;
 }
 
 static Option make_row_option(const st_conv_desc& d, int rows_per_tile) {
@@ -453,7 +467,7 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       ti.k_steps_per_split = op.steps_per_split;
       ti.item_begin = fused_total;
       ti.item_count = (int64_t)ti.tiles_m * ti.tiles_n * op.split;
-      ti.xcd_group_by = xcd_group_choice(descs[t], ti);
+      xcd_block_choice(descs[t], &ti);
       fused_total += ti.item_count;
     }
     if (fused_total >= ((int64_t)1 << 31)) {

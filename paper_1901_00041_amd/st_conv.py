@@ -58,7 +58,7 @@ class st_tenant_info(ctypes.Structure):
                 ("k_steps", ctypes.c_int32), ("k_steps_per_split", ctypes.c_int32),
                 ("item_begin", ctypes.c_int64), ("item_count", ctypes.c_int64),
                 ("row_tiled", ctypes.c_int32), ("rows_per_tile", ctypes.c_int32),
-                ("xcd_group_by", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("xcd_blocks_m", ctypes.c_int32), ("xcd_blocks_n", ctypes.c_int32)]
 
 
 class st_plan_info(ctypes.Structure):

@@ -64,27 +64,27 @@ def test_config_totals_match_generator(cfg):
         assert (ti.M, ti.Ngemm, ti.Kgemm) == s.gemm and (ti.P, ti.Q) == (s.P, s.Q)
 
 
-def _xcd_group_by(shape, ti):
-    """Which operand's re-reads the placement avoids: the slice shared by more tiles, weighted by its size."""
+def _xcd_blocks(shape, ti):
+    """The block grid restated: most blocks first (at most 8, powers of two per side, no more blocks than tiles per
+    side), then fewest bytes fetched over all XCDs (activations once per filter-block column, filters once per
+    pixel-block row), then the smaller pixel-block count."""
     es = 4 if shape.dtype == "f32" else 2
     w_bytes = ti.Ngemm * ti.Kgemm * es
     x_bytes = shape.N * shape.C * shape.H * shape.W * es
-    save_w = (min(ti.tiles_m, 8) - 1) * w_bytes
-    save_x = (min(ti.tiles_n, 8) - 1) * x_bytes
-    if save_w <= 0 and save_x <= 0:
-        return 0
-    return 1 if save_w >= save_x else 2
+    cands = [(a, b) for a in (1, 2, 4, 8) for b in (1, 2, 4, 8) if a * b <= 8 and a <= ti.tiles_m and b <= ti.tiles_n]
+    return min(cands, key=lambda ab: (-ab[0] * ab[1], ab[1] * x_bytes + ab[0] * w_bytes, ab[0]))
 
 
-def _xcd_deal(rows, phase, mode, split_k):
+def _xcd_deal(rows, phase, ti):
     """The placement rule restated: rows (tenant, k, tile_m, tile_n, 0) in nested order are dealt to launch
-    positions; position q (XCD (phase+q) % 8) takes the next row whose group prefers that XCD, else the next
+    positions; position q (XCD (phase+q) % 8) takes the next row whose block prefers that XCD, else the next
     row of the XCD with most rows left (lowest XCD on ties)."""
-    if mode == 0 or len(rows) < 2:
+    a, b = ti.xcd_blocks_m, ti.xcd_blocks_n
+    if a * b <= 1 or len(rows) < 2:
         return list(rows)
     buckets = [[] for _ in range(8)]
     for r in rows:
-        g = (r[3] if mode == 1 else r[2]) * split_k + r[1]
+        g = (r[2] * a // ti.tiles_m) * b + (r[3] * b // ti.tiles_n)
         buckets[g % 8].append(r)
     out = []
     for q in range(len(rows)):
@@ -114,8 +114,8 @@ def _expected_tenant_major(plan, n_tenants, shapes=None):
         assert ti.item_begin == len(rows) and ti.item_count == ti.tiles_m * ti.tiles_n * ti.split_k
         mine = [(t, s, tm, tn, 0) for tm in range(ti.tiles_m) for tn in range(ti.tiles_n) for s in range(ti.split_k)]
         if shapes is not None:
-            assert ti.xcd_group_by == _xcd_group_by(shapes[t], ti)
-        rows.extend(_xcd_deal(mine, 0, ti.xcd_group_by, ti.split_k))
+            assert (ti.xcd_blocks_m, ti.xcd_blocks_n) == _xcd_blocks(shapes[t], ti)
+        rows.extend(_xcd_deal(mine, 0, ti))
     return np.array(rows, dtype=np.int64).reshape(-1, 5)
 
 
@@ -171,28 +171,32 @@ def test_work_lists_bit_exact(cfg, opts):
     assert np.array_equal(_as_rows(sc.st_conv_plan_worklist(p2, 0)), fused)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4])
-def test_fused_list_keeps_operand_slices_on_one_xcd(cfg):
-    """Workgroup b of a launch runs on XCD b mod 8.  For every tenant whose items form one run of the fused list
-    and whose sharing groups divide evenly among the XCDs (a multiple of 8 groups, or a divisor of 8), the items
-    that read one operand slice sit on as few XCDs as an even spread of the work allows: 1, or 8 / groups."""
-    shapes = synth.config_shapes(cfg)
-    p = _host_plan(shapes)
-    fused = _as_rows(sc.st_conv_plan_worklist(p, 0))
-    checked = 0
-    for t in range(len(shapes)):
-        ti = sc.st_conv_plan_tenant_info(p, t)
-        pos = np.nonzero(fused[:, 0] == t)[0]
-        n_groups = (ti.tiles_n if ti.xcd_group_by == 1 else ti.tiles_m) * ti.split_k
-        if ti.xcd_group_by == 0 or len(pos) != pos[-1] - pos[0] + 1 or (n_groups % 8 != 0 and 8 % n_groups != 0):
-            continue
-        bound = 1 if n_groups % 8 == 0 else 8 // n_groups
-        key = fused[pos, 3] if ti.xcd_group_by == 1 else fused[pos, 2]
-        group = key * ti.split_k + fused[pos, 1]
-        for g in np.unique(group):
-            assert len(set((pos[group == g] % 8).tolist())) <= bound, f"tenant {t} group {g} spans more than {bound} XCDs"
-        checked += 1
-    assert checked > 0
+def test_fused_list_keeps_tile_blocks_on_one_xcd():
+    """Workgroup b of a launch runs on XCD b mod 8.  For every tenant whose items form one run of the fused list and
+    whose 8 blocks hold equally many items, every block sits on exactly one XCD; for every other tenant with 8 blocks,
+    most of each block's items sit on the block's own XCD (the rest were dealt to XCDs that had run dry)."""
+    exact = loose = 0
+    for cfg in (2, 3, 4):
+        shapes = synth.config_shapes(cfg)
+        p = _host_plan(shapes)
+        fused = _as_rows(sc.st_conv_plan_worklist(p, 0))
+        for t in range(len(shapes)):
+            ti = sc.st_conv_plan_tenant_info(p, t)
+            pos = np.nonzero(fused[:, 0] == t)[0]
+            a, b = ti.xcd_blocks_m, ti.xcd_blocks_n
+            if a * b != 8 or len(pos) != pos[-1] - pos[0] + 1:
+                continue
+            block = (fused[pos, 2] * a // ti.tiles_m) * b + (fused[pos, 3] * b // ti.tiles_n)
+            sizes = [int((block == g).sum()) for g in range(8)]
+            for g in range(8):
+                on = pos[block == g] % 8
+                if len(set(sizes)) == 1:
+                    assert len(set(on.tolist())) == 1, f"cfg {cfg} tenant {t} block {g} spans several XCDs"
+                else:
+                    assert (on == g).sum() * 2 >= len(on) or sizes[g] > 2 * min(sizes), f"cfg {cfg} tenant {t} block {g}"
+            exact += len(set(sizes)) == 1
+            loose += len(set(sizes)) != 1
+    assert exact > 0 and exact + loose > 3
 
 
 def test_fused_order_longest_first():
