@@ -268,13 +268,20 @@ void st_pipeline_destroy(st_pipeline* pipeline);
  *
  * Tiles are chosen per stage (all ops of that stage, over all sequences, planned together as st_conv_plan would).
  * A queue is stage-major, longest work item first within a stage.  There is either one queue for the whole chip,
- * or (the default from 8 sequences on, on a whole 8-XCD device) one queue per XCD with sequence s in queue
- * s mod 8, served only by the workgroups that run on that XCD: a sequence's activations then stay in one XCD's
- * L2, and a consumer only has to drop its compute unit's vector cache instead of making the whole L2 coherent.
- * Workgroups claim entries in queue order, so the launch needs no co-residency guarantee; every dependency wait
+ * or (the default from 8 sequences on, on a whole 8-XCD device) queues per XCD with sequence s on XCD s mod 8,
+ * served only by the workgroups that run on that XCD: a sequence's activations then stay in one XCD's L2, and a
+ * finished work item is announced through that L2 (a flag per work item) instead of through memory.  An XCD's
+ * entries are split in two queues: the first workgroup to arrive on a compute unit serves the "exclusive" queue,
+ * later arrivals the "shared" one, and a stage's entries go to the shared queue only beyond one per compute unit
+ * (two tiles sharing a compute unit each run markedly slower than one that has it to itself); a first workgroup
+ * whose queue is exhausted goes on with the shared queue.  Activations written during the launch are read with
+ * device-scope loads, so no cache is invalidated between stages.
+ * Workgroups claim entries in queue order, so the launch needs no guarantee that all of them are resident at once
+ * (with queues per XCD: that at least one compute unit of every XCD holds two, eventually); every dependency wait
  * is bounded by a wall-clock limit (default 100 ms) and a poll count, after which the launch abandons the pass:
- * every workgroup leaves, outputs are incomplete, and st_chain_aborted reports it.  Same ops + same inputs => outputs bitwise identical from run to run, and bitwise
- * identical to running the stages one st_conv_run at a time with the same tiles. */
+ * every workgroup leaves, outputs are incomplete, and st_chain_aborted reports it.  Same ops + same inputs =>
+ * outputs bitwise identical from run to run, and bitwise identical to running the stages one st_conv_run at a
+ * time with the same tiles. */
 typedef enum { ST_OP_CONV = 0, ST_OP_MAXPOOL = 1 } st_op_kind;
 
 typedef struct st_chain_op {
@@ -295,8 +302,10 @@ typedef struct st_chain_info {
   int64_t flops, bytes;      /* sums over the convolution ops (as st_plan_info)                       */
   int64_t workspace_bytes;   /* split-K partial tiles and counters (shared by a sequence's stages)    */
   int32_t host_only;
-  int32_t n_queues;          /* 1, or 8: one queue per XCD                                            */
-  int64_t queue_begin[9];    /* queue q is entries [queue_begin[q], queue_begin[q+1]) of the work list */
+  int32_t n_queues;          /* 1, or 8: queues per XCD                                               */
+  int64_t queue_begin[9];    /* XCD (or the one queue) q owns entries [queue_begin[q], queue_begin[q+1]) */
+  int64_t shared_begin[8];   /* ... of which [queue_begin[q], shared_begin[q]) are its exclusive queue and    */
+                             /* [shared_begin[q], queue_begin[q+1]) its shared queue (empty with one queue)   */
 } st_chain_info;
 
 typedef struct st_chain_op_info {

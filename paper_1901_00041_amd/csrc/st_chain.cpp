@@ -24,11 +24,14 @@ struct st_chain {
   uint32_t ctl_slots = 0;                    // slots of one control block (kChainCtlStride words each)
   uint32_t spin_limit_ticks = 10000000u;     // 100 ms of the 100 MHz constant clock
   uint32_t flags = 0;
-  int n_queues = 1;
-  uint32_t qbegin[kNumXCDs + 1] = {};        // queue q is items[qbegin[q] .. qbegin[q + 1])
+  int n_queues = 1;                          // 1, or kNumXCDs
+  // one queue: items[qbegin[0] .. qbegin[1]).  A queue per XCD: XCD x's entries are items[qbegin[2x] .. qbegin[2x + 2]),
+  // the exclusive queue first (2x), then the shared one (2x + 1)
+  uint32_t qbegin[2 * kNumXCDs + 1] = {};
   int workgroups = 0;
   unsigned run_parity = 0;                   // control block the next run uses
   int64_t runs = 0;
+  uint32_t run_number = 0;                   // number of the most recent run (per-item completion flags hold it)
   // device
   char* d_arena = nullptr;
   TenantDev* d_ops = nullptr;
@@ -36,6 +39,8 @@ struct st_chain {
   uint32_t* d_ctl[2] = {nullptr, nullptr};
   char* d_counters = nullptr;                // split-K arrival counters of all sequences
   size_t counters_bytes = 0;
+  uint32_t* d_item_flags = nullptr;          // one completion flag per work item (queue per XCD only)
+  size_t item_flags_bytes = 0;
 };
 
 static st_status validate_pool(const st_conv_desc& d, int i) {
@@ -115,12 +120,22 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
       return fail(ST_ERR_UNSUPPORTED, "one queue per XCD needs a device with %d XCDs, this one shows %d", kNumXCDs, n_xcd);
     }
     c->n_queues = (want_queues == 2 || (want_queues == 0 && n_xcd == kNumXCDs && c->n_sequences >= kNumXCDs)) ? kNumXCDs : 1;
-    c->flags = c->n_queues > 1 ? kChainFlagAcquireL1 : kChainFlagAcquireAgent;
-    std::vector<std::vector<st_work_item>> queues((size_t)c->n_queues);
+    // a queue per XCD: producer and consumer of a sequence share that XCD's L2, and completion travels through it
+    c->flags = c->n_queues > 1 ? kChainFlagLocalFlags : 0u;
+    // compute units per XCD and workgroups that fit one: a stage's entries go to an XCD's shared queue only beyond
+    // one per compute unit (and never when a compute unit holds one workgroup only)
+    // (a queue per XCD is only used on a whole device: kNumCUs compute units, max_wg / kNumCUs workgroups on each)
+    const int cus_per_xcd = kNumCUs / kNumXCDs;
+    const bool two_per_cu = max_wg / kNumCUs >= 2;
+    const int n_sub = c->n_queues > 1 ? 2 * kNumXCDs : 1;
+    std::vector<std::vector<st_work_item>> queues((size_t)n_sub);
     std::map<int, std::vector<int>> by_stage;          // stage -> op indices, caller's order
     for (int i = 0; i < n_ops; ++i) by_stage[ops[i].stage].push_back(i);
     c->n_stages = (int)by_stage.size();
     std::vector<int64_t> done((size_t)c->n_sequences, 0);          // work items of each sequence in earlier stages
+    // completion flags: one per work item; a sequence's items of one stage are contiguous, op after op
+    int64_t flag_total = 0;
+    std::vector<int64_t> prev_begin((size_t)c->n_sequences, 0), prev_count((size_t)c->n_sequences, 0);
     // split-K workspace of a sequence: the largest need of any of its stages (its stages never overlap in time)
     std::vector<int64_t> seq_ws((size_t)c->n_sequences, 0), seq_ct((size_t)c->n_sequences, 0);
     struct Use { int op; int64_t ws_off, ct_off; };
@@ -159,10 +174,11 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
         c->bytes += sp->info[j].bytes;
       }
       // queue: the stage's convolution items in the fused order (longest first), then its max-pool items
+      std::vector<std::vector<st_work_item>> stage_q((size_t)c->n_queues);
       for (const st_work_item& it : sp->items_fused) {
         st_work_item g = it;
         g.tenant = (uint16_t)conv_ops[it.tenant];
-        queues[(size_t)(ops[g.tenant].sequence % c->n_queues)].push_back(g);
+        stage_q[(size_t)(ops[g.tenant].sequence % c->n_queues)].push_back(g);
       }
       for (int i : pool_ops) {
         const st_conv_desc& d = ops[i].conv;
@@ -184,6 +200,7 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
         T.P = P; T.Q = Q; T.PQ = P * Q; T.M = (int32_t)total;
         T.in_dtype = d.in_dtype; T.out_dtype = d.in_dtype;
         T.cfg = kChainPoolCfg; T.split_k = 1;
+        T.tiles_m = (int32_t)n_it; T.tiles_n = 1;
         T.x_bytes = (uint32_t)((int64_t)d.N * d.H * d.W * d.C * es);
         T.y_bytes = (uint32_t)((int64_t)d.N * P * Q * d.C * es);
         T.chain_seq = q;
@@ -192,11 +209,35 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
         for (int64_t k = 0; k < n_it; ++k) {
           st_work_item g;
           g.tenant = (uint16_t)i; g.k_split_idx = 0; g.tile_m = (uint32_t)k; g.tile_n = 0; g.reserved = 0;
-          queues[(size_t)(q % c->n_queues)].push_back(g);
+          stage_q[(size_t)(q % c->n_queues)].push_back(g);
         }
         stage_items[q] += n_it;
       }
+      // one queue: as is.  A queue per XCD: the stage's entries go, one compute unit's worth at a time, alternately
+      // to the XCD's exclusive and shared queue, so a stage with no more entries than compute units never shares one
+      for (int x = 0; x < c->n_queues; ++x) {
+        const std::vector<st_work_item>& sq = stage_q[(size_t)x];
+        for (size_t k = 0; k < sq.size(); ++k) {
+          const int cls = (c->n_queues > 1 && two_per_cu) ? (int)((k / (size_t)cus_per_xcd) & 1u) : 0;
+          queues[(size_t)(c->n_queues > 1 ? 2 * x + cls : 0)].push_back(sq[k]);
+        }
+      }
+      std::vector<int64_t> cursor((size_t)c->n_sequences, 0), stage_begin((size_t)c->n_sequences, 0);
       for (int q = 0; q < c->n_sequences; ++q) {
+        cursor[q] = stage_begin[q] = flag_total;
+        flag_total += stage_items[q];
+      }
+      for (int i : kv.second) {
+        const int q = ops[i].sequence;
+        TenantDev& T = c->table[i];
+        T.chain_flag_base = (uint32_t)cursor[q];
+        cursor[q] += c->info[i].item_count;
+        T.chain_dep_begin = (uint32_t)prev_begin[q];
+        T.chain_dep_count = (uint32_t)prev_count[q];
+        T.chain_reserved = 0;
+      }
+      for (int q = 0; q < c->n_sequences; ++q) {
+        if (stage_items[q] > 0) { prev_begin[q] = stage_begin[q]; prev_count[q] = stage_items[q]; }
         done[q] += stage_items[q];
         seq_ws[q] = std::max(seq_ws[q], stage_ws[q]);
         seq_ct[q] = std::max(seq_ct[q], stage_ct[q]);
@@ -208,14 +249,14 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
       if (total_items >= ((int64_t)1 << 31)) status = fail(ST_ERR_UNSUPPORTED, "more than 2^31 work items");
     }
     if (status == ST_OK) {
-      for (int qi = 0; qi < c->n_queues; ++qi) {
+      for (int qi = 0; qi < n_sub; ++qi) {
         c->qbegin[qi] = (uint32_t)c->items.size();
         c->items.insert(c->items.end(), queues[(size_t)qi].begin(), queues[(size_t)qi].end());
       }
-      for (int qi = c->n_queues; qi <= kNumXCDs; ++qi) c->qbegin[qi] = (uint32_t)c->items.size();
+      for (int qi = n_sub; qi <= 2 * kNumXCDs; ++qi) c->qbegin[qi] = (uint32_t)c->items.size();
     }
     if (status == ST_OK) {
-      // arena: [op table][queue][control block x2][split-K counters][split-K partial tiles]
+      // arena: [op table][queue][control block x2][split-K counters][completion flags][split-K partial tiles]
       auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
       c->ctl_slots = (uint32_t)(kChainCtlSeq + c->n_sequences);
       int64_t ws_total = 0, ct_total = 0;
@@ -227,8 +268,10 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
       c->workspace_bytes = ws_total * 4 + ct_total * 4;
       const size_t off_items = up((size_t)n_ops * sizeof(TenantDev));
       const size_t off_ctl = off_items + up(c->items.size() * sizeof(st_work_item));
-      const size_t off_ct = off_ctl + up((size_t)c->ctl_slots * kChainCtlStride * 4 * 2);
-      const size_t off_ws = off_ct + up((size_t)ct_total * 4);
+      const size_t ctl_words = (size_t)c->ctl_slots * kChainCtlStride + kChainRankWords;   // one control block
+      const size_t off_ct = off_ctl + up(ctl_words * 4 * 2);
+      const size_t off_flags = off_ct + up((size_t)ct_total * 4);
+      const size_t off_ws = off_flags + up(c->n_queues > 1 ? c->items.size() * 4 : 0);
       const size_t total = off_ws + (size_t)ws_total * 4;
       if (!host_only && n_ops > 0) {
         hipError_t e = hipMalloc((void**)&c->d_arena, total);
@@ -247,9 +290,13 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
           c->d_ops = (TenantDev*)c->d_arena;
           c->d_items = (st_work_item*)(c->d_arena + off_items);
           c->d_ctl[0] = (uint32_t*)(c->d_arena + off_ctl);
-          c->d_ctl[1] = c->d_ctl[0] + (size_t)c->ctl_slots * kChainCtlStride;
+          c->d_ctl[1] = c->d_ctl[0] + ctl_words;
           c->d_counters = c->d_arena + off_ct;
           c->counters_bytes = (size_t)ct_total * 4;
+          if (c->n_queues > 1) {
+            c->d_item_flags = (uint32_t*)(c->d_arena + off_flags);
+            c->item_flags_bytes = c->items.size() * 4;
+          }
         }
       }
       // one queue: no more workgroups than entries; a queue per XCD: every resident slot (workgroup b runs on XCD
@@ -273,8 +320,13 @@ static st_status chain_launch(st_chain* c, void* stream, uint64_t* prof_dev) {
   if (c->host_only) return fail(ST_ERR_UNSUPPORTED, "chain was built host-only and cannot run");
   if (c->items.empty()) return ST_OK;
   const unsigned p = c->run_parity;
+  if (++c->run_number == 0u) {
+    // the run numbers have wrapped: forget every flag of the old numbering (a fill kernel, so a capture may hold it)
+    if (c->d_item_flags) ST_HIP((hipError_t)launch_zero(c->d_item_flags, (int64_t)((c->item_flags_bytes + 15) & ~(size_t)15), stream));
+    c->run_number = 1u;
+  }
   ST_HIP((hipError_t)launch_chain(c->d_ops, c->d_items, c->qbegin, (uint32_t)c->n_queues, c->d_ctl[p], c->d_ctl[p ^ 1u], c->ctl_slots,
-                                  c->spin_limit_ticks, c->flags, c->workgroups, stream, prof_dev));
+                                  c->d_item_flags, c->run_number, c->spin_limit_ticks, c->flags, c->workgroups, stream, prof_dev));
   c->run_parity = p ^ 1u;
   ++c->runs;
   return ST_OK;
@@ -314,7 +366,7 @@ extern "C" st_status st_chain_aborted(st_chain* chain, int32_t* aborted) {
   const bool incomplete = chain->runs > 0 && done != (uint32_t)chain->items.size();
   if (flag[0] | flag[1] | (incomplete ? 1u : 0u)) {
     // an abandoned pass has left its queue head, its sequence counters and some split-K arrival counters anywhere
-    ST_HIP(hipMemset(chain->d_ctl[0], 0, (size_t)chain->ctl_slots * kChainCtlStride * 4 * 2));
+    ST_HIP(hipMemset(chain->d_ctl[0], 0, ((size_t)chain->ctl_slots * kChainCtlStride + kChainRankWords) * 4 * 2));
     if (chain->counters_bytes) ST_HIP(hipMemset(chain->d_counters, 0, chain->counters_bytes));
     chain->runs = 0;
     *aborted = 1;
@@ -342,7 +394,8 @@ extern "C" st_status st_chain_get_info(const st_chain* chain, st_chain_info* out
   out->workspace_bytes = chain->workspace_bytes;
   out->host_only = chain->host_only ? 1 : 0;
   out->n_queues = chain->n_queues;
-  for (int q = 0; q <= kNumXCDs; ++q) out->queue_begin[q] = chain->qbegin[q];
+  for (int q = 0; q <= kNumXCDs; ++q) out->queue_begin[q] = chain->qbegin[chain->n_queues > 1 ? 2 * q : std::min(q, 1)];
+  for (int q = 0; q < kNumXCDs; ++q) out->shared_begin[q] = chain->n_queues > 1 ? chain->qbegin[2 * q + 1] : out->queue_begin[q + 1];
   return ST_OK;
 }
 

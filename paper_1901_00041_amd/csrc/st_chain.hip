@@ -13,9 +13,14 @@
 // either expires the waiter raises the abort flag, and every workgroup leaves at its next claim or wait.  A workgroup
 // also claims at most n_items + 1 times.  So the kernel always exits, whatever the clock or the counters do.
 //
-// Memory: producers write their outputs through to memory (device-scope stores) and wait for them before one
-// device-scope atomic bumps the sequence's counter; a consumer that has seen the counter reach its threshold
-// invalidates its caches (device-scope acquire) before it loads.
+// Memory: producers write their outputs through to memory (device-scope stores) and wait for them before they
+// signal; consumers read activations, residuals and partial tiles with device-scope loads (CoherentActs), which
+// never stop at a vector cache and take from an L2 only what that L2 holds newer than memory, so no cache is ever
+// invalidated.  (The workgroup-scope invalidate does nothing for a workgroup that sits on one compute unit, and
+// the device-scope one also empties the XCD's L2 of the filters: measured 1-2 us per work item.)  The signal is,
+// with one queue for the chip, a device-scope atomic on the sequence's counter; with queues per XCD, where producer
+// and consumer share one L2, a plain store of the run's number into the work item's own flag, which the consumer's
+// polls then find in that L2 (0.25 us from store to sight, against 0.6 us and more through memory).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,11 +37,13 @@ struct ChainArgs {
   uint32_t* ctl;          // this run's control block
   uint32_t* ctl_other;    // the next run's: cleared by workgroup 0
   uint64_t* prof;         // kProfSlots stamps per queue entry, or nullptr
-  uint32_t ctl_slots;     // slots of a control block (one live word per 256-byte slot)
+  uint32_t* item_flags;   // kChainFlagLocalFlags: one completion flag per work item, holding the number of the run that set it
+  uint32_t run_number;    // this run's number (never 0)
+  uint32_t ctl_slots;     // 256-byte slots of a control block (one live word each); kChainRankWords dense words follow them
   uint32_t spin_limit;    // ticks of the 100 MHz constant clock a dependency wait may last
   uint32_t flags;         // kChainFlag*
-  uint32_t n_queues;      // 1: one queue for the whole chip; kNumXCDs: queue x is served by the workgroups on XCD x
-  uint32_t qbegin[kNumXCDs + 1];   // queue q is items[qbegin[q] .. qbegin[q + 1])
+  uint32_t n_queues;      // 1: one queue for the whole chip; kNumXCDs: two queues per XCD (see st_chain_kernel)
+  uint32_t qbegin[2 * kNumXCDs + 1];   // queue j is items[qbegin[j] .. qbegin[j + 1]); with one queue only j = 0 is used
 };
 
 constexpr uint32_t kChainMaxPolls = 1u << 22;   // a poll takes a microsecond or so: seconds, far beyond any real wait
@@ -52,7 +59,7 @@ template <int DT>
 __device__ __forceinline__ void pool_item(ConstOp& T, const st_work_item it) {
   const int64_t idx = (int64_t)it.tile_m * kThreads + work_thread_id();
   if (idx >= (int64_t)T.M) return;
-  const u32x4 v = maxpool_vector<DT>(T.x, idx, T.H, T.W, T.C, T.P, T.Q, T.R, T.stride, T.pad);
+  const u32x4 v = maxpool_vector<DT, kAuxDeviceCoherent>(T.x, T.x_bytes, idx, T.H, T.W, T.C, T.P, T.Q, T.R, T.stride, T.pad);
   __builtin_amdgcn_raw_buffer_store_b128(v, make_rsrc(T.y, T.y_bytes), (int)((uint32_t)idx * 16u), 0, kAuxDeviceCoherent);
 }
 
@@ -66,9 +73,9 @@ __device__ __forceinline__ void chain_item(ConstOp& T, const st_work_item it, ch
     }
   } else {
     switch (T.in_dtype) {
-      case ST_DT_BF16: run_dtype<ST_DT_BF16>(T, it, smem, prof); break;
-      case ST_DT_F16: run_dtype<ST_DT_F16>(T, it, smem, prof); break;
-      default: run_dtype<ST_DT_F32>(T, it, smem, prof); break;
+      case ST_DT_BF16: run_dtype<ST_DT_BF16, CoherentActs>(T, it, smem, prof); break;
+      case ST_DT_F16: run_dtype<ST_DT_F16, CoherentActs>(T, it, smem, prof); break;
+      default: run_dtype<ST_DT_F32, CoherentActs>(T, it, smem, prof); break;
     }
   }
 }
@@ -111,6 +118,13 @@ __device__ __forceinline__ uint32_t chain_claim(const ChainArgs& a, uint32_t q, 
   return idx;
 }
 
+// With one queue per XCD, the XCD's entries are split in two: queue 2x ("exclusive") and queue 2x + 1 ("shared").  Two
+// workgroups fit a compute unit, and two tiles that share one run 20-45 % slower each than a tile that has it to
+// itself; a stage of a sequence often has no more tiles than the XCD has compute units.  So the first workgroup to
+// arrive on a compute unit serves the exclusive queue and every later one the shared queue, and the host puts a
+// stage's entries into the shared queue only beyond one per compute unit.  A first workgroup whose queue is exhausted
+// goes on with the shared queue; should no second workgroup become resident on the whole XCD within the wait limit
+// while shared entries are due, the pass is abandoned and reported like any other expired wait.
 __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[kSmemBytes];
   __shared__ uint32_t s_msg[2];
@@ -119,87 +133,133 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
     // the control block of the NEXT run (runs alternate between two blocks; the stream orders them)
     for (uint32_t i = (uint32_t)tid; i < a.ctl_slots; i += kThreads)
       __hip_atomic_store(&a.ctl_other[i * kChainCtlStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t i = (uint32_t)tid; i < (uint32_t)kChainRankWords; i += kThreads)
+      __hip_atomic_store(&a.ctl_other[a.ctl_slots * kChainCtlStride + i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  // which queue this workgroup serves: with one queue per XCD, the one of the XCD it runs on
-  uint32_t q = 0u;
+  // which queues this workgroup serves, in which order
+  uint32_t q_first = 0u, n_serve = 1u;
   if (a.n_queues > 1u) {
-    q = (uint32_t)__builtin_amdgcn_s_getreg(0x1814) & 15u;       // XCC_ID
-    if (q >= a.n_queues) {
-      // an XCD this launch was not planned for: its workgroups must not touch any queue (the light acquire below is
-      // only valid inside one XCD); the pass is reported as abandoned
+    const uint32_t xcc = (uint32_t)__builtin_amdgcn_s_getreg(0x1814) & 15u;       // XCC_ID
+    if (xcc >= a.n_queues) {
+      // an XCD this launch was not planned for: its workgroups must not touch any queue (completion flags are only
+      // valid inside one XCD); the pass is reported as abandoned
       if (tid == 0) __hip_atomic_store(&a.ctl[kChainCtlAbort * kChainCtlStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
     }
-  }
-  const uint32_t qb = a.qbegin[q], qe = a.qbegin[q + 1];
-  uint32_t next = 0xffffffffu;            // thread 0: the entry claimed ahead
-  uint32_t n_done = 0u;
-  if (tid == 0) next = chain_claim(a, q, qb, qe);
-  for (uint32_t round = 0; round <= qe - qb; ++round) {
-    if (tid == 0) s_msg[0] = next;
-    __syncthreads();
-    const uint32_t idx = __builtin_amdgcn_readfirstlane(s_msg[0]);
-    if (idx >= qe) break;
-    ConstItem* ip = (ConstItem*)(a.items + idx);
-    st_work_item it;
-    it.tenant = ip->tenant;
-    it.k_split_idx = ip->k_split_idx;
-    it.tile_m = ip->tile_m;
-    it.tile_n = ip->tile_n;
-    it.reserved = 0u;
-    ConstOp& T = *(ConstOp*)(a.ops + it.tenant);
-    uint64_t* prof = a.prof ? a.prof + (size_t)idx * kProfSlots : nullptr;
-    uint64_t waited = 0;
-    if (T.chain_need != 0u) {
-      const uint32_t touched = prefetch_filters(T, it, tid);
-      if (tid == 0) {
-        uint32_t* ctr = a.ctl + (kChainCtlSeq + T.chain_seq) * kChainCtlStride;
-        const uint32_t need = T.chain_need;
-        const uint64_t t0 = wall_clock64();
-        uint32_t ok = 1u, polls = 0u;
-        // Device-scope atomics are carried out at the memory side: a load that stops at the XCD's L2 never sees the
-        // counter move (measured: such polls time out), so every poll is a device-scope load, a round trip to memory.
-        auto poll = [&]() -> uint32_t { return __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-        while ((int32_t)(poll() - need) < 0) {
-          // the abort flag and the clock are looked at on every 16th poll (every few microseconds)
-          if ((++polls & 15u) != 0u) { __builtin_amdgcn_s_sleep(4); continue; }
-          if (__hip_atomic_load(&a.ctl[kChainCtlAbort * kChainCtlStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) { ok = 0u; break; }
-          if (wall_clock64() - t0 > (uint64_t)a.spin_limit || polls > kChainMaxPolls) {
-            __hip_atomic_store(&a.ctl[kChainCtlAbort * kChainCtlStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = 0u;
-            break;
-          }
-          __builtin_amdgcn_s_sleep(4);
-        }
-        waited = wall_clock64() - t0;
-        // What the producers wrote (through, to the L2 and to memory) must not be served from a stale cache.  One
-        // queue per XCD: producer and consumer share the XCD's L2, so only this compute unit's vector cache can be
-        // stale (the acquire of a workgroup spread over compute units).  One queue for the chip: device-scope acquire.
-        if (a.flags & kChainFlagAcquireAgent) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        else if (a.flags & kChainFlagAcquireL1) asm volatile("buffer_inv sc0" ::: "memory");
-        s_msg[1] = ok;
-      }
-      __syncthreads();
-      asm volatile("" ::"v"(touched));      // the prefetch loads are complete (and not optimised away)
-      if (s_msg[1] == 0u) break;
-    }
-    if (T.cfg == kChainPoolCfg && prof && tid == 0) prof[4] = wall_clock64();
-    chain_item(T, it, smem, prof);
-    // The following entry is claimed now: the atomic's round trip then overlaps the wait for this entry's stores.
-    // (Claimed before the entry's work it would sit at the head of the in-order memory counter and hold up the
-    // entry's first operand loads by its whole round trip.)
-    if (tid == 0) next = chain_claim(a, q, qb, qe);
-    // Completion.  Outputs were stored write-through; channel counts that are not a multiple of 8 take an epilogue
-    // with plain stores and need the full release fence.
-    if ((a.flags & kChainFlagReleaseFence) != 0u || (T.cfg != kChainPoolCfg && (T.K & 7) != 0)) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __builtin_amdgcn_s_waitcnt(0);          // every store of this thread has been acknowledged
-    __syncthreads();                        // ... of every thread; also: smem and s_msg are free again
-    ++n_done;
     if (tid == 0) {
-      __hip_atomic_fetch_add(a.ctl + (kChainCtlSeq + T.chain_seq) * kChainCtlStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (prof) {
-        prof[7] = waited;
-        if (T.cfg == kChainPoolCfg) prof[6] = wall_clock64();
+      // shader engine, shader array and compute unit of HW_ID: one of kChainRankWords / kNumXCDs keys per XCD
+      const uint32_t cu = ((uint32_t)__builtin_amdgcn_s_getreg(0xF804) >> 8) & 255u;
+      s_msg[0] = __hip_atomic_fetch_add(&a.ctl[a.ctl_slots * kChainCtlStride + xcc * 256u + cu], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const uint32_t arrived = __builtin_amdgcn_readfirstlane(s_msg[0]);
+    __syncthreads();
+    q_first = 2u * xcc + (arrived != 0u ? 1u : 0u);
+    // only the first workgroup of a compute unit goes on to the other queue (a later one would bring back the
+    // sharing that the exclusive queue avoids)
+    n_serve = arrived != 0u ? 1u : 2u;
+  }
+  uint32_t n_done = 0u;
+  bool left = false;
+  for (uint32_t serve = 0; serve < n_serve && !left; ++serve) {
+    const uint32_t q = q_first ^ serve;
+    const uint32_t qb = a.qbegin[q], qe = a.qbegin[q + 1];
+    uint32_t next = 0xffffffffu;            // thread 0: the entry claimed ahead
+    if (tid == 0) next = chain_claim(a, q, qb, qe);
+    for (uint32_t round = 0; round <= qe - qb; ++round) {
+      if (tid == 0) s_msg[0] = next;
+      __syncthreads();
+      const uint32_t idx = __builtin_amdgcn_readfirstlane(s_msg[0]);
+      if (idx >= qe) break;
+      ConstItem* ip = (ConstItem*)(a.items + idx);
+      st_work_item it;
+      it.tenant = ip->tenant;
+      it.k_split_idx = ip->k_split_idx;
+      it.tile_m = ip->tile_m;
+      it.tile_n = ip->tile_n;
+      it.reserved = 0u;
+      ConstOp& T = *(ConstOp*)(a.ops + it.tenant);
+      uint64_t* prof = a.prof ? a.prof + (size_t)idx * kProfSlots : nullptr;
+      uint64_t waited = 0;
+      if (T.chain_need != 0u) {
+        // Wavefront 0 looks at the dependency: with flags, at those of the sequence's previous stage, 64 at a time from
+        // the first that was not yet set (they were stored by workgroups of this XCD and sit, newer than memory, in
+        // its L2, where a device-scope load finds them; such a load never stops at the vector cache); with a
+        // counter, at the sequence's count of finished entries (bumped by device-scope atomics, carried out at the
+        // memory side; a workgroup-scope load would stop at the vector cache and never see it move).
+        const bool by_flags = (a.flags & kChainFlagLocalFlags) != 0u;
+        const uint32_t* f = a.item_flags + T.chain_dep_begin;
+        const uint32_t n = T.chain_dep_count, run = a.run_number, need = T.chain_need;
+        const uint32_t* ctr = a.ctl + (kChainCtlSeq + T.chain_seq) * kChainCtlStride;
+        uint32_t c0 = 0u;                     // flags before c0 are known to be set
+        auto satisfied = [&]() -> bool {      // wavefront 0 only, uniform
+          if (!by_flags) return (int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - need) >= 0;
+          while (c0 < n) {
+            const uint32_t c = c0 + (uint32_t)tid;
+            const bool unset = (c < n) && __hip_atomic_load(f + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != run;
+            if (__builtin_amdgcn_ballot_w64(unset) != 0ull) return false;
+            c0 += 64u;
+          }
+          return true;
+        };
+        // first look: an entry whose dependency is already complete starts at once
+        if (tid < 64) {
+          const bool ready = satisfied();
+          if (tid == 0) s_msg[1] = ready ? 1u : 2u;
+        }
+        __syncthreads();
+        const uint32_t first = s_msg[1];
+        if (first == 2u) {
+          __syncthreads();                    // s_msg[1] has been read by everyone
+          // not yet: pull the filter slab closer while waiting
+          const uint32_t touched = prefetch_filters(T, it, tid);
+          if (tid < 64) {
+            const uint64_t t0 = wall_clock64();
+            uint32_t ok = 1u, polls = 0u;
+            while (!satisfied()) {
+              // the abort flag and the clock are looked at on every 16th poll (every few microseconds)
+              if ((++polls & 15u) != 0u) { __builtin_amdgcn_s_sleep(2); continue; }
+              if (__hip_atomic_load(&a.ctl[kChainCtlAbort * kChainCtlStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) { ok = 0u; break; }
+              if (wall_clock64() - t0 > (uint64_t)a.spin_limit || polls > kChainMaxPolls) {
+                if (tid == 0) __hip_atomic_store(&a.ctl[kChainCtlAbort * kChainCtlStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0u;
+                break;
+              }
+              __builtin_amdgcn_s_sleep(2);
+            }
+            waited = wall_clock64() - t0;
+            if (tid == 0) s_msg[1] = ok;
+          }
+          // No cache is invalidated here: everything an entry reads that this launch wrote (activations, residuals,
+          // split-K partial tiles) is read with device-scope loads, and everything else did not change.
+          __syncthreads();
+          asm volatile("" ::"v"(touched));      // the prefetch loads are complete (and not optimised away)
+          if (s_msg[1] == 0u) { left = true; break; }
+        }
+      }
+      if (T.cfg == kChainPoolCfg && prof && tid == 0) prof[4] = wall_clock64();
+      chain_item(T, it, smem, prof);
+      // Completion.  Outputs were stored write-through; channel counts that are not a multiple of 8 take an epilogue
+      // with plain stores and need the release fence (write-back of the L2).
+      if (T.cfg != kChainPoolCfg && (T.K & 7) != 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __builtin_amdgcn_s_waitcnt(0);          // every store of this thread has been acknowledged
+      __syncthreads();                        // ... of every thread; also: smem and s_msg are free again
+      ++n_done;
+      if (tid == 0) {
+        if ((a.flags & kChainFlagLocalFlags) != 0u) {
+          const uint32_t pos = ((uint32_t)it.tile_m * (uint32_t)T.tiles_n + (uint32_t)it.tile_n) * (uint32_t)T.split_k + (uint32_t)it.k_split_idx;
+          __hip_atomic_store(a.item_flags + T.chain_flag_base + pos, a.run_number, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        } else {
+          __hip_atomic_fetch_add(a.ctl + (kChainCtlSeq + T.chain_seq) * kChainCtlStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // The following entry is claimed only now.  The claim is a round trip to memory: issued before the entry's
+        // work it sits in front of the first operand loads in the in-order memory counter; issued before the
+        // completion signal (even as early as the end of the K loop: measured) it delays every dependant.
+        next = chain_claim(a, q, qb, qe);
+        if (prof) {
+          prof[7] = waited;
+          if (T.cfg == kChainPoolCfg) prof[6] = wall_clock64();
+        }
       }
     }
   }
@@ -223,20 +283,26 @@ int chain_max_workgroups(int* out_workgroups, int* out_xcds) {
 }
 
 int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const uint32_t* qbegin, uint32_t n_queues, uint32_t* ctl,
-                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t spin_limit_ticks, uint32_t flags, int grid, void* stream,
-                 uint64_t* prof_dev) {
-  if (grid <= 0 || n_queues < 1 || n_queues > (uint32_t)kNumXCDs || qbegin[n_queues] == 0u) return 0;
+                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number, uint32_t spin_limit_ticks,
+                 uint32_t flags, int grid, void* stream, uint64_t* prof_dev) {
+  if (n_queues != 1u && n_queues != (uint32_t)kNumXCDs) return (int)hipErrorInvalidValue;
+  const uint32_t n_sub = n_queues == 1u ? 1u : 2u * n_queues;
+  if (grid <= 0 || qbegin[n_sub] == 0u) return 0;
+  if (((flags & kChainFlagLocalFlags) != 0u) != (n_queues > 1u)) return (int)hipErrorInvalidValue;
+  if ((flags & kChainFlagLocalFlags) != 0u && (item_flags == nullptr || run_number == 0u)) return (int)hipErrorInvalidValue;
   ChainArgs a;
   a.ops = ops_dev;
   a.items = items_dev;
   a.ctl = ctl;
   a.ctl_other = ctl_other;
   a.prof = prof_dev;
+  a.item_flags = item_flags;
+  a.run_number = run_number;
   a.ctl_slots = ctl_slots;
   a.spin_limit = spin_limit_ticks;
   a.flags = flags;
   a.n_queues = n_queues;
-  for (int q = 0; q <= kNumXCDs; ++q) a.qbegin[q] = qbegin[q <= (int)n_queues ? q : (int)n_queues];
+  for (uint32_t j = 0; j <= 2u * kNumXCDs; ++j) a.qbegin[j] = qbegin[j <= n_sub ? j : n_sub];
   hipLaunchKernelGGL(st_chain_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }

@@ -68,6 +68,11 @@ struct TenantDev {
   // chain kernel only (st_chain.hip); the per-plan kernel ignores them
   int32_t chain_seq;          // sequence whose completion counter this op's work items wait on and bump
   uint32_t chain_need;        // work items of that sequence that must be complete before this op's may start
+  // one completion flag per work item (queue per XCD): work item (tile_m, tile_n, slice) of this op owns flag
+  // chain_flag_base + (tile_m * tiles_n + tile_n) * split_k + slice; the op may start once the flags
+  // [chain_dep_begin, chain_dep_begin + chain_dep_count) of the sequence's previous stage all hold the run's number
+  uint32_t chain_flag_base, chain_dep_begin, chain_dep_count;
+  uint32_t chain_reserved;
 };
 static_assert(sizeof(TenantDev) % 8 == 0, "TenantDev must keep pointer alignment in arrays");
 
@@ -77,17 +82,19 @@ int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int
 // Persistent chain launch (st_chain.hip).  ctl / ctl_other: this run's and the next run's control block.  A block is
 // ctl_slots slots of kChainCtlStride 32-bit words (256 bytes) with one live word each, so that the words hundreds of
 // workgroups poll and bump sit in different cache lines and memory channels: slot kChainCtlAbort the abort flag,
-// kChainCtlDone the count of completed work items, kChainCtlHead + q the head of queue q, kChainCtlSeq + s the
-// completion counter of sequence s.  qbegin: n_queues + 1 queue boundaries (host array).
+// kChainCtlDone the count of completed work items, kChainCtlHead + j the head of queue j, kChainCtlSeq + s the
+// completion counter of sequence s; kChainRankWords dense words follow the slots (how many workgroups have arrived
+// on each compute unit).  n_queues is 1 or kNumXCDs; qbegin (host array) holds the boundaries of the one queue, or of
+// the 2 * kNumXCDs queues (XCD x: exclusive queue 2x, shared queue 2x + 1).  item_flags / run_number:
+// the per-item completion flags and this run's number (kChainFlagLocalFlags only; else nullptr / anything).
 constexpr int kChainCtlStride = 64;
-constexpr int kChainCtlAbort = 1, kChainCtlDone = 2, kChainCtlHead = 4, kChainCtlSeq = 16;
-constexpr uint32_t kChainFlagReleaseFence = 1u;   // device-scope release fence before every completion
-constexpr uint32_t kChainFlagAcquireAgent = 2u;   // device-scope acquire after a dependency wait
-constexpr uint32_t kChainFlagAcquireL1 = 4u;      // invalidate only the compute unit's vector cache after a wait
+constexpr int kChainCtlAbort = 1, kChainCtlDone = 2, kChainCtlHead = 4, kChainCtlSeq = 4 + 2 * kNumXCDs;
+constexpr int kChainRankWords = kNumXCDs * 256;   // arrival counts per (XCD, compute unit key), dense, after the slots
+constexpr uint32_t kChainFlagLocalFlags = 4u;     // completion travels through per-item flags in the XCD's own L2
 int chain_max_workgroups(int* out_workgroups, int* out_xcds);
 int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const uint32_t* qbegin, uint32_t n_queues, uint32_t* ctl,
-                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t spin_limit_ticks, uint32_t flags, int grid, void* stream,
-                 uint64_t* prof_dev);
+                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number, uint32_t spin_limit_ticks,
+                 uint32_t flags, int grid, void* stream, uint64_t* prof_dev);
 int launch_empty(void* stream);
 // Allocation-free path: device address of the current GPU's fixed scratch array (looked up on first use per device),
 // host bytes -> device through kernel arguments (sizes rounded up to 16 bytes; dst 16-byte aligned), and a zero fill.

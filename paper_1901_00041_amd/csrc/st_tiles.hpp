@@ -148,6 +148,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 constexpr int kAuxDeviceCoherent = 16;   // sc1
+// How a tile reads activations (x and the residual): what another kernel wrote before this launch can be read
+// through the caches (PlainActs); what other workgroups of the SAME launch write (the chain kernel) must be read
+// with device-scope loads, which never stop at the compute unit's vector cache and take from the L2 only what that
+// L2 itself holds newer than memory (CoherentActs).  Outputs are stored write-through either way; filters never
+// change during a launch and always go through the caches.
+struct PlainActs { static constexpr int kActAux = 0; };
+struct CoherentActs { static constexpr int kActAux = kAuxDeviceCoherent; };
 
 // floor(n / d) for 0 <= n < 2^31 with the planner's multiplier m = floor(2^(31+L)/d)+1, L = ceil(log2 d)
 __device__ __forceinline__ int fast_div(int n, uint32_t m, int L) {
@@ -164,7 +171,7 @@ constexpr uint32_t kInvalidOffset = 0x80000000u;   // >= num_records of every bu
 // im2col row m0 and first filter n0; rows at or past m_end are not stored.
 // The transposition buffer `smem` holds MT/PASSES pixel rows; with PASSES > 1 the tile is written out in
 // that many slices of consecutive pixel rows.
-template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, int CAP = kSmemBytes, class Acc, class TD>
+template <int MT, int NT, int BM, int BN, int MF, int PASSES = 1, int CAP = kSmemBytes, class POL = PlainActs, class Acc, class TD>
 __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], int m0, int m_end, int n0, int wm0,
                                               int wn0, int lrow, int lk, int tid, char* smem, uint64_t* prof = nullptr) {
   constexpr int NG = (MF == 32) ? 4 : 1;
@@ -238,7 +245,7 @@ __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], i
           const int v = u * kThreads + tid;
           const int m = m0 + v / (NT / 4), ch = n0 + (v % (NT / 4)) * 4;
           const bool ok = (MP * (NT / 4) % kThreads == 0 || v < MP * (NT / 4)) & (m < m_end) & (ch < Kf);
-          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset), 0, 0);
+          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 4u : kInvalidOffset), 0, POL::kActAux);
         }
       } else {
 #pragma unroll
@@ -246,7 +253,7 @@ __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], i
           const int v = u * kThreads + tid;
           const int m = m0 + v / (NT / 8), ch = n0 + (v % (NT / 8)) * 8;
           const bool ok = (MP * (NT / 8) % kThreads == 0 || v < MP * (NT / 8)) & (m < m_end) & (ch < Kf);
-          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset), 0, 0);
+          rpre[u] = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)(ok ? ((uint32_t)m * (uint32_t)Kf + (uint32_t)ch) * 2u : kInvalidOffset), 0, POL::kActAux);
         }
       }
     }
@@ -289,7 +296,7 @@ __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], i
         if (has_res) {
 #pragma unroll
           for (int u = 0; u < UB; ++u)
-            a[u] += __builtin_bit_cast(f32x4, kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0));
+            a[u] += __builtin_bit_cast(f32x4, kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, POL::kActAux));
         }
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
@@ -323,7 +330,7 @@ __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], i
         if (has_res) {
 #pragma unroll
           for (int u = 0; u < UB; ++u) {
-            const u32x4 r = kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, 0);
+            const u32x4 r = kPrefetchRes ? rpre[u0 + u] : __builtin_amdgcn_raw_buffer_load_b128(rr, (int)off[u], 0, POL::kActAux);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const uint16_t h0 = (uint16_t)(r[e >> 1] >> (16 * (e & 1))), h1 = (uint16_t)(r[2 + (e >> 1)] >> (16 * (e & 1)));
@@ -373,7 +380,11 @@ __device__ __forceinline__ void tile_epilogue(const TD& T, Acc (&acc)[BM][BN], i
             if (has_res) {
               const float* rp = (const float*)T.res + o;
 _Pragma("unroll")
-              for (int e = 0; e < 4; ++e) if (e < nv) v[e] += rp[e];
+              for (int e = 0; e < 4; ++e)
+                if (e < nv) {
+                  if constexpr (POL::kActAux == 0) v[e] += rp[e];
+                  else v[e] += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(T.res, T.y_bytes), (int)((uint32_t)(o + e) * 4u), 0, POL::kActAux));
+                }
             }
             if (relu)
 _Pragma("unroll")
@@ -389,7 +400,13 @@ _Pragma("unroll")
             if (has_res) {
               const uint16_t* rp = (const uint16_t*)T.res + o;
 _Pragma("unroll")
-              for (int e = 0; e < 4; ++e) if (e < nv) v[e] += isbf ? bf16_bits_to_f32(rp[e]) : f16_bits_to_f32(rp[e]);
+              for (int e = 0; e < 4; ++e)
+                if (e < nv) {
+                  uint16_t rb;
+                  if constexpr (POL::kActAux == 0) rb = rp[e];
+                  else rb = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(make_rsrc(T.res, T.y_bytes), (int)((uint32_t)(o + e) * 2u), 0, POL::kActAux);
+                  v[e] += isbf ? bf16_bits_to_f32(rb) : f16_bits_to_f32(rb);
+                }
             }
             if (relu)
 _Pragma("unroll")
@@ -423,7 +440,7 @@ _Pragma("unroll")
 // quarter of each K step (sub-step = wavefront index), so every staged byte is read from LDS exactly once.  After
 // the K loop the four partial tiles are summed through LDS, in wavefront order, into the accumulators the
 // pixel/filter division would have produced, and everything downstream (split-K, epilogue) is unchanged.
-template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false, class TD>
+template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false, class POL = PlainActs, class TD>
 __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int ES = ElemOf<DT>::ES;
   constexpr int VEC = 16 / ES;          // elements per 16-byte vector
@@ -526,7 +543,7 @@ __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, ch
       for (int i = 0; i < A_IT; ++i) {
         const bool ok = kin & ((unsigned)(a_h0[i] + kr) < (unsigned)H) & ((unsigned)(a_w0[i] + ksx) < (unsigned)W);
         const uint32_t off = ok ? (uint32_t)(a_base[i] + koff) * ES : kInvalidOffset;
-        qa[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
+        qa[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, POL::kActAux);
       }
 #pragma unroll
       for (int i = 0; i < B_IT; ++i) {
@@ -549,8 +566,8 @@ __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, ch
         for (int i = 0; i < A_IT; ++i) {
           const bool ok = kin & ((unsigned)(a_h0[i] + kr) < (unsigned)H) & ((unsigned)(a_w0[i] + ksx) < (unsigned)W);
           const uint32_t off = ok ? (uint32_t)(a_base[i] + koff) * ES : kInvalidOffset;
-          if constexpr (ES == 4) ea[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rx, (int)off, 0, 0);
-          else ea[i][e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (int)off, 0, 0);
+          if constexpr (ES == 4) ea[i][e] = __builtin_amdgcn_raw_buffer_load_b32(rx, (int)off, 0, POL::kActAux);
+          else ea[i][e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (int)off, 0, POL::kActAux);
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
@@ -770,7 +787,7 @@ __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, ch
   }
 
   // ---- epilogue: (+ residual) -> ReLU -> cast -> store ---------------------------------------------
-  tile_epilogue<MT, NT, BM, BN, MF>(T, acc, m0, T.M, n0, wm0, wn0, lrow, lk, tid, smem, prof);
+  tile_epilogue<MT, NT, BM, BN, MF, 1, kSmemBytes, POL>(T, acc, m0, T.M, n0, wm0, wn0, lrow, lk, tid, smem, prof);
   if (prof && tid == 0) {
     prof[3] = __builtin_readcyclecounter();
     prof[6] = wall_clock64();
@@ -801,7 +818,7 @@ __device__ __forceinline__ u32x4 window128(const u32x4& lo, const u32x4& hi, int
 // 64 filters are copied once into an LDS array [filter][r][32] padded with zeros, and the MFMA operands
 // are assembled from LDS.  K is laid out as r*32 + (s*C + c).  Eligibility is decided by the planner:
 // 16-bit types, 8 <= S*C <= 32, W*C*2 a multiple of 16, stride*C even, LDS footprint.
-template <int DT, class TD>
+template <int DT, class POL = PlainActs, class TD>
 __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int MT = 128, NT = 64, MF = 32, WM = 64, WN = 32, BM = 2, BN = 1, KR = 32;
   const int RT = T.rows_per_tile;                    // output rows per work item (1..kRowsPerTile)
@@ -865,7 +882,7 @@ __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item i
     const int sj = 16 * j - lpad;                           // byte position of this vector in the row data
     const bool ok = (v < total_rv) & ((unsigned)(h_first + r) < (unsigned)H) & (sj >= 0) & (sj + 16 <= rowb);
     mine = (v < total_rv) & !((sl != 0) & ((j == jl) | (j == jr)));      // the straddlers are written below
-    return __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(r) + (uint32_t)sj : kInvalidOffset), 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(r) + (uint32_t)sj : kInvalidOffset), 0, POL::kActAux);
   };
   auto row_store = [&](int v, const u32x4& d, bool mine) {
     if (mine) *(u32x4*)(sX + v * 16) = d;
@@ -895,7 +912,7 @@ __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item i
   for (int u = 0; u < RB; ++u) drow[u] = row_load(u * kThreads + tid, rmine[u]);
   if (sl != 0) {
     const bool ok = (fr < NR) & ((unsigned)(h_first + fr) < (unsigned)H);
-    dfix = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(fr) + (uint32_t)(fside ? rowb - 16 : 0) : kInvalidOffset), 0, 0);
+    dfix = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? row_base(fr) + (uint32_t)(fside ? rowb - 16 : 0) : kInvalidOffset), 0, POL::kActAux);
   }
 #pragma unroll
   for (int u = 0; u < RW; ++u) dw[u] = w_load((tid >> 2) + 64 * u);
@@ -988,7 +1005,7 @@ __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item i
     };
     if (nh > 1) k_loop(std::integral_constant<int, 2>{}); else k_loop(std::integral_constant<int, 1>{});
     const int mrow = (n * P + p0 + rt) * Q;
-    tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES, kStageBytes>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
+    tile_epilogue<MT, NT, BM, BN, MF, EPI_PASSES, kStageBytes, POL>(T, acc, mrow + q0, mrow + q_end, n0, wm0, wn0, lrow, lk, tid, smem);
   }
   if (prof && tid == 0) {
     prof[2] = prof[3] = __builtin_readcyclecounter();
@@ -996,50 +1013,52 @@ __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item i
   }
 }
 
-template <int CFG, int DT, bool GENERIC, bool KW = false, class TD>
+template <int CFG, int DT, bool GENERIC, bool KW = false, class POL = PlainActs, class TD>
 __device__ __forceinline__ void run_cfg(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr TileShape s = kTileShapes[CFG];
-  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW>(T, it, smem, prof);
+  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW, POL>(T, it, smem, prof);
 }
 
 // TD is TenantDev, or TenantDev qualified with the constant address space (records that no launch in flight
 // modifies: every field read is then a scalar load, however many stores, atomics and barriers surround it).
-template <int DT, class TD>
+template <int DT, class POL = PlainActs, class TD>
 __device__ __forceinline__ void run_dtype(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   if (T.vec_ok) {
     switch (T.cfg) {
-      case 0: run_cfg<0, DT, false>(T, it, smem, prof); break;
-      case 1: run_cfg<1, DT, false>(T, it, smem, prof); break;
-      case 2: run_cfg<2, DT, false>(T, it, smem, prof); break;
-      case 3: run_cfg<3, DT, false>(T, it, smem, prof); break;
+      case 0: run_cfg<0, DT, false, false, POL>(T, it, smem, prof); break;
+      case 1: run_cfg<1, DT, false, false, POL>(T, it, smem, prof); break;
+      case 2: run_cfg<2, DT, false, false, POL>(T, it, smem, prof); break;
+      case 3: run_cfg<3, DT, false, false, POL>(T, it, smem, prof); break;
       // the two smallest tiles split each K step across the wavefronts (see KW above) when the planner found
       // the K loop long enough to repay the final sum of the four partial tiles
       case 4:
-        if (T.k_across_waves) run_cfg<4, DT, false, true>(T, it, smem, prof);
-        else run_cfg<4, DT, false>(T, it, smem, prof);
+        if (T.k_across_waves) run_cfg<4, DT, false, true, POL>(T, it, smem, prof);
+        else run_cfg<4, DT, false, false, POL>(T, it, smem, prof);
         break;
       default:
-        if (T.k_across_waves) run_cfg<5, DT, false, true>(T, it, smem, prof);
-        else run_cfg<5, DT, false>(T, it, smem, prof);
+        if (T.k_across_waves) run_cfg<5, DT, false, true, POL>(T, it, smem, prof);
+        else run_cfg<5, DT, false, false, POL>(T, it, smem, prof);
         break;
     }
   } else {
     // few-channel layers: the row tile when the planner found it eligible, else element-wise gathers
     // (which exist for the two tile shapes marked in kGenericCfg)
     if constexpr (DT != ST_DT_F32) {
-      if (T.cfg == kRowCfg) { conv_tile_rows<DT>(T, it, smem, prof); return; }
+      if (T.cfg == kRowCfg) { conv_tile_rows<DT, POL>(T, it, smem, prof); return; }
     }
-    if (T.cfg == 1) run_cfg<1, DT, true>(T, it, smem, prof);
-    else run_cfg<3, DT, true>(T, it, smem, prof);
+    if (T.cfg == 1) run_cfg<1, DT, true, false, POL>(T, it, smem, prof);
+    else run_cfg<3, DT, true, false, POL>(T, it, smem, prof);
   }
 }
 
 // ---- max-pool of one output vector (chain kernel) ---------------------------------------------------
 // NHWC max-pool, one 16-byte vector of channels of one output pixel: idx counts (n, p, q, channel vector) with the
 // channel vector fastest.  Padding never wins; the result is a copy of the winning input's bits.
-template <int DT>
-__device__ __forceinline__ u32x4 maxpool_vector(const void* __restrict__ xv, int64_t idx, int H, int W, int C, int P, int Q,
-                                                int win, int stride, int pad) {
+// AUX: cache policy of the input loads (0: through the caches; kAuxDeviceCoherent: device-scope loads, for an input
+// that other workgroups of the same launch wrote); x_bytes < 2^31 is the size of the input.
+template <int DT, int AUX = 0>
+__device__ __forceinline__ u32x4 maxpool_vector(const void* __restrict__ xv, uint32_t x_bytes, int64_t idx, int H, int W, int C, int P,
+                                                int Q, int win, int stride, int pad) {
   constexpr int ES = ElemOf<DT>::ES, VEC = 16 / ES;
   const int CV = C / VEC;
   const int cv = (int)(idx % CV);
@@ -1059,7 +1078,10 @@ __device__ __forceinline__ u32x4 maxpool_vector(const void* __restrict__ xv, int
     for (int s = 0; s < win; ++s) {
       const int w = q * stride - pad + s;
       if ((unsigned)w >= (unsigned)W) continue;
-      const u32x4 raw = *(const u32x4*)((const char*)xv + ((((int64_t)n * H + h) * W + w) * C + (int64_t)cv * VEC) * ES);
+      const int64_t xoff = ((((int64_t)n * H + h) * W + w) * C + (int64_t)cv * VEC) * ES;
+      u32x4 raw;
+      if constexpr (AUX == 0) raw = *(const u32x4*)((const char*)xv + xoff);
+      else raw = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc(xv, x_bytes), (int)(uint32_t)xoff, 0, AUX);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         uint32_t b;

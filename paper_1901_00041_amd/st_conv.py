@@ -75,7 +75,8 @@ class st_chain_info(ctypes.Structure):
     _fields_ = [("n_ops", ctypes.c_int32), ("n_sequences", ctypes.c_int32), ("n_stages", ctypes.c_int32),
                 ("workgroups", ctypes.c_int32), ("n_items", ctypes.c_int64), ("flops", ctypes.c_int64),
                 ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64), ("host_only", ctypes.c_int32),
-                ("n_queues", ctypes.c_int32), ("queue_begin", ctypes.c_int64 * 9)]
+                ("n_queues", ctypes.c_int32), ("queue_begin", ctypes.c_int64 * 9),
+                ("shared_begin", ctypes.c_int64 * 8)]
 
 
 class st_chain_op_info(ctypes.Structure):

@@ -57,25 +57,36 @@ def _check_chain(ops, chain):
             assert got == want and len(mine) == len(want), i
         else:
             assert sorted(mine["tile_m"].tolist()) == list(range(oi.item_count)) and (mine["tile_n"] == 0).all()
-    # every queue is stage-major and holds whole sequences (sequence s in queue s mod n_queues)
+    # an XCD's entries (or the one queue's) hold whole sequences (sequence s on XCD s mod n_queues); its exclusive and
+    # its shared queue are each stage-major; a stage's entries go to the shared queue only beyond one per compute
+    # unit (32 per XCD), 32 at a time alternately
     qb = list(info.queue_begin)[:info.n_queues + 1]
+    sb = list(info.shared_begin)[:info.n_queues]
     assert qb[0] == 0 and qb[-1] == len(items) and info.n_queues in (1, 8)
     for q in range(info.n_queues):
-        seg = items["tenant"][qb[q]:qb[q + 1]]
-        assert (np.diff(np.array([ops[t].stage for t in seg])) >= 0).all()
-        assert all(ops[t].sequence % info.n_queues == q for t in seg)
+        assert qb[q] <= sb[q] <= qb[q + 1]
+        if info.n_queues == 1:
+            assert sb[q] == qb[q + 1]
+        excl, shared = items["tenant"][qb[q]:sb[q]], items["tenant"][sb[q]:qb[q + 1]]
+        for seg in (excl, shared):
+            assert (np.diff(np.array([ops[t].stage for t in seg])) >= 0).all()
+            assert all(ops[t].sequence % info.n_queues == q for t in seg)
+        if info.n_queues > 1:
+            n_e = {st: 0 for st in {o.stage for o in ops}}
+            n_s = dict(n_e)
+            for t in excl:
+                n_e[ops[t].stage] += 1
+            for t in shared:
+                n_s[ops[t].stage] += 1
+            for st in n_e:
+                n = n_e[st] + n_s[st]
+                assert n_e[st] == sum(min(32, max(0, n - 64 * r)) for r in range(n // 64 + 1)), (q, st, n, n_e[st])
     # thresholds: items of the op's sequence in strictly earlier stages
     for i, oi in enumerate(per_op):
         need = sum(p.item_count for j, p in enumerate(per_op) if p.sequence == oi.sequence and p.stage < oi.stage)
         assert oi.need == need, (i, oi.need, need)
-    # progress: when entry k is reached, the entries it waits for all sit before it (in its own queue: a sequence
-    # lives in one queue)
-    seq_of = np.array([ops[t].sequence for t in items["tenant"]])
-    for q in set(seq_of.tolist()):
-        pos = np.nonzero(seq_of == q)[0]
-        counts_before = np.arange(len(pos))            # entries of this sequence before each of its entries
-        need = np.array([per_op[t].need for t in items["tenant"][pos]])
-        assert (need <= counts_before).all()
+    # progress: an entry waits only for entries of strictly earlier stages (the thresholds above), and every queue is
+    # stage-major and claimed in order, so the unfinished entry of the lowest stage is always claimable
     return per_op
 
 

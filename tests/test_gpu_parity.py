@@ -454,3 +454,40 @@ def test_many_tenants_in_one_launch(torch):
     _sync(torch)
     for i, t in enumerate(tenants):
         helpers.check_tenant(t, f"tenant {i} of 300")
+
+
+def _random_shapes(seed: int, n: int):
+    """Seeded assortment of small layers: every dtype, odd sizes, strides 1-3, paddings 0-3, filters 1x1 to 5x5 (square
+    or not), channel counts that are and are not multiples of the 16-byte vector."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        dtype = ("bf16", "f16", "f32")[int(rng.integers(3))]
+        out_dtype = "f32" if rng.random() < 0.6 else dtype
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        C = int(rng.choice([1, 3, 4, 8, 12, 16, 24, 40, 64, 72]))
+        K = int(rng.choice([1, 5, 8, 16, 24, 40, 64, 100, 136]))
+        out.append(ConvShape(int(rng.integers(1, 4)), C, H, W, K, R, S, stride, pad, dtype, out_dtype))
+    return out
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes_in_one_launch(torch, seed):
+    """Forty seeded random layers in one fused launch (planner's own choices), and again with a forced small tile and
+    split-K: every element against the oracle."""
+    from tests import helpers
+    shapes = _random_shapes(seed, 40)
+    tenants = [helpers.Tenant(s, synth.gen_input(99, t, seed, s), synth.gen_weight(99, t, seed, s), relu=bool(t % 3 == 0))
+               for t, s in enumerate(shapes)]
+    for opts in ({}, {"tile_cfg": 5, "split_k": 2}, {"tile_cfg": 1, "order": 2}):
+        for t in tenants:
+            t.clear()
+        plan = helpers.plan_for(tenants, **opts)
+        sc.st_conv_run(plan)
+        _sync(torch)
+        for i, t in enumerate(tenants):
+            helpers.check_tenant(t, f"seed {seed} tenant {i} {t.shape} opts={opts}")
