@@ -112,8 +112,9 @@ def test_chain_matches_layer_launches_bitwise_on_reused_buffers(chain_queues):
 
 def test_chain_mixed_small_ops():
     """Two sequences of unequal length with fp32 and 16-bit layers, a residual, a filter count that is not a multiple of
-    8 (the epilogue with plain stores), a max-pool in the middle and two independent ops in one stage: every op against
-    the oracle on the tensors it read."""
+    8 (the epilogue with plain stores, also reading a residual), channel counts that take element-wise gathers, a max-pool
+    in the middle and two independent ops in one stage, with one queue and with queues per XCD: every op against the
+    oracle on the tensors it read."""
     import torch
     from oracle import oracle
     from tests import helpers
@@ -130,6 +131,11 @@ def test_chain_mixed_small_ops():
         (1, 0, ConvShape(1, 12, 10, 10, 20, 3, 3, 1, 1, "f32", "f32"), "in1", "e", None, True),     # 20 filters: plain stores
         (1, 2, ConvShape(1, 20, 10, 10, 36, 3, 3, 1, 1, "f32", "f32"), "e", "f", None, False),
         (1, 4, ConvShape(1, 36, 5, 5, 16, 1, 1, 1, 0, "f32", "f32"), "fp", "g", None, True),
+        # element-wise gathers and the plain-store epilogue reading a residual, fp32 and 16-bit
+        (1, 5, ConvShape(1, 16, 5, 5, 20, 3, 3, 1, 1, "f32", "f32"), "g", "h", None, False),
+        (1, 6, ConvShape(1, 20, 5, 5, 20, 3, 3, 1, 1, "f32", "f32"), "h", "i", "h", True),
+        (0, 4, ConvShape(2, 40, 9, 11, 12, 1, 1, 1, 0, "bf16", "bf16"), "d", "j", None, False),
+        (0, 5, ConvShape(2, 12, 9, 11, 12, 3, 3, 1, 1, "bf16", "bf16"), "j", "k", "j", True),
     ]
     bufs = {"in0": helpers.to_device_nhwc(synth.gen_input(98, 0, 0, specs[0][2]), "bf16"),
             "in1": helpers.to_device_nhwc(synth.gen_input(98, 1, 0, specs[4][2]), "f32"),
@@ -147,11 +153,14 @@ def test_chain_mixed_small_ops():
         keep.append(dw)
     pool = sc.make_desc(1, 36, 10, 10, 36, 3, 3, 2, 1, "f32", "f32", bufs["f"], None, bufs["fp"])
     ops.append(sc.make_chain_op(sc.ST_OP_MAXPOOL, 1, 3, pool))
-    for opts in (None, sc.plan_opts(tile_cfg=4, split_k=2), sc.plan_opts(tile_cfg=6, split_k=3)):
+    # one queue for the chip (two sequences), then queues per XCD forced (completion flags, exclusive/shared queues)
+    for opts in (None, sc.plan_opts(tile_cfg=4, split_k=2), sc.plan_opts(tile_cfg=6, split_k=3),
+                 sc.plan_opts(chain_queues=2), sc.plan_opts(tile_cfg=4, split_k=2, chain_queues=2), sc.plan_opts(tile_cfg=5, split_k=3, chain_queues=2)):
         for k, b in bufs.items():
             if not k.startswith("in"):
                 b.fill_(float("nan"))
         chain = sc.Chain(ops, opts, keep=[bufs, keep])
+        assert chain.info().n_queues == (8 if opts is not None and opts.chain_queues == 2 else 1)
         for _ in range(3):
             chain.run()
         torch.cuda.synchronize()
@@ -161,5 +170,51 @@ def test_chain_mixed_small_ops():
             got = _nchw(bufs[dst])
             tol = helpers.tolerance(s, ref)
             err = np.abs(got - ref)
-            assert np.isfinite(got).all() and (err <= tol).all(), f"op {i} opts {opts and (opts.tile_cfg, opts.split_k)}: max err {err.max():.3e}"
+            assert np.isfinite(got).all() and (err <= tol).all(), f"op {i} opts {opts and (opts.tile_cfg, opts.split_k, opts.chain_queues)}: max err {err.max():.3e}"
         assert np.array_equal(_nchw(bufs["fp"]), oracle.maxpool2d(_nchw(bufs["f"]), 3, 2, 1))
+
+
+def test_chain_sixteen_sequences_on_pingpong_buffers():
+    """Sixteen sequences (two per XCD) of four dependent layers that write back and forth between two buffers (every
+    stage overwrites what the stage before it read), sizes differing per sequence: many passes, each bitwise equal to
+    the same layers run stage by stage as ordinary fused launches."""
+    import torch
+    from tests import helpers
+    n_seq, n_stage = 16, 4
+    rng = np.random.default_rng(7)
+    seqs = []
+    for q in range(n_seq):
+        C = int(rng.choice([16, 32, 64]))
+        H, W = int(rng.integers(7, 15)), int(rng.integers(7, 15))
+        s = ConvShape(int(rng.integers(1, 3)), C, H, W, C, 3, 3, 1, 1, "bf16", "bf16")
+        x = helpers.to_device_nhwc(synth.gen_input(97, q, 0, s), "bf16")
+        a, b = torch.zeros_like(x), torch.zeros_like(x)
+        ws = [helpers.to_device_nhwc(synth.gen_weight(97, q, l, s, 2.0), "bf16") for l in range(n_stage)]
+        seqs.append((s, x, a, b, ws))
+    stage_descs = []
+    for l in range(n_stage):
+        descs = []
+        for (s, x, a, b, ws) in seqs:
+            src = x if l == 0 else (a if l % 2 == 1 else b)
+            dst = a if l % 2 == 0 else b
+            descs.append(sc.make_desc(s.N, s.C, s.H, s.W, s.K, 3, 3, 1, 1, "bf16", "bf16", src, ws[l], dst, None, sc.ST_EPI_RELU))
+        stage_descs.append(descs)
+    plans = [sc.st_conv_plan(d, None, keep=[seqs]) for d in stage_descs]
+    for p in plans:
+        sc.st_conv_run(p)
+    torch.cuda.synchronize()
+    want = [(a.clone(), b.clone()) for (_, _, a, b, _) in seqs]
+    ops = [sc.make_chain_op(sc.ST_OP_CONV, q, l, stage_descs[l][q]) for l in range(n_stage) for q in range(n_seq)]
+    chain = sc.Chain(ops, None, keep=[seqs])
+    info = chain.info()
+    assert info.n_queues == 8 and info.n_sequences == n_seq
+    for rep in range(20):
+        if rep % 5 == 0:
+            for (_, _, a, b, _) in seqs:
+                a.zero_(); b.zero_()
+        chain.run()
+        if rep % 5 == 4:
+            torch.cuda.synchronize()
+            for q, (_, _, a, b, _) in enumerate(seqs):
+                assert torch.equal(a, want[q][0]) and torch.equal(b, want[q][1]), f"pass {rep}, sequence {q}"
+    assert not chain.aborted()
