@@ -1072,25 +1072,36 @@ __device__ __forceinline__ u32x4 maxpool_vector(const void* __restrict__ xv, uin
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { best[e] = 0.f; bits[e] = 0u; }
   bool any = false;
-  for (int r = 0; r < win; ++r) {
-    const int h = p * stride - pad + r;
-    if ((unsigned)h >= (unsigned)H) continue;
-    for (int s = 0; s < win; ++s) {
-      const int w = q * stride - pad + s;
-      if ((unsigned)w >= (unsigned)W) continue;
+  // The taps are visited row by row as a plain loop would, but nine at a time: all nine loads are issued before the
+  // first is looked at (taps outside the image or past the window get an out-of-range offset and are skipped), so a
+  // 3x3 window costs one memory round trip, not nine.
+  constexpr int B = 9;
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(xv, x_bytes);
+  const int taps = win * win;
+  for (int t0 = 0; t0 < taps; t0 += B) {
+    u32x4 raw[B];
+    bool ok[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      const int tp = t0 + u;
+      const int r = tp / win, sx = tp - r * win;
+      const int h = p * stride - pad + r, w = q * stride - pad + sx;
+      ok[u] = (tp < taps) & ((unsigned)h < (unsigned)H) & ((unsigned)w < (unsigned)W);
       const int64_t xoff = ((((int64_t)n * H + h) * W + w) * C + (int64_t)cv * VEC) * ES;
-      u32x4 raw;
-      if constexpr (AUX == 0) raw = *(const u32x4*)((const char*)xv + xoff);
-      else raw = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc(xv, x_bytes), (int)(uint32_t)xoff, 0, AUX);
+      raw[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok[u] ? (uint32_t)xoff : kInvalidOffset), 0, AUX);
+    }
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      if (!ok[u]) continue;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         uint32_t b;
         float v;
         if constexpr (ES == 4) {
-          b = raw[e];
+          b = raw[u][e];
           v = __builtin_bit_cast(float, b);
         } else {
-          b = (raw[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+          b = (raw[u][e >> 1] >> (16 * (e & 1))) & 0xffffu;
           v = (DT == ST_DT_BF16) ? bf16_bits_to_f32((uint16_t)b) : f16_bits_to_f32((uint16_t)b);
         }
         if (!any || v > best[e]) { best[e] = v; bits[e] = b; }
