@@ -22,6 +22,7 @@ constexpr int kNumTileCfgs = 7;
 constexpr int kRowCfg = 6;         // the row tile for few-channel layers (conv_tile_rows): 128-pixel segments of
                                    // kRowsPerTile consecutive output rows x 64 filters, one filter row per K step
 constexpr int kChainPoolCfg = 7;   // chain kernel only: TenantDev.cfg of a max-pool op (not a convolution tile shape)
+constexpr int kScalarTapMinItems = 320;   // work items of a launch from which the scalar form of the tap search is used
 constexpr int kRowsPerTile = 4;    // most output rows one row-tile work item may take (the planner picks 1, 2 or 4)
 constexpr TileShape kTileShapes[kNumTileCfgs] = {
     {128, 128, 2, 2, 32, 128, 2},  // 0: wave tile 64x64
@@ -53,7 +54,8 @@ struct TenantDev {
   int32_t cfg, split_k, k_steps, k_steps_per_split;
   int32_t tiles_m, tiles_n;
   int32_t vec_ok;        // 1: C is a multiple of the 16-byte vector width, gathers use 16-byte loads
-  int32_t tap_uniform;   // 1: C is a multiple of the K step, so each step lies within one filter tap
+  int32_t tap_uniform;   // 1: each K step lies within one filter tap (C is a multiple of the step) AND the planner
+                         //    wants the tap found with scalar arithmetic (small tiles only; see kScalarTapMinItems)
   int32_t shift_c, shift_s;   // floor(n/d) = ((n * magic) >> 31) >> shift, for d = C and d = S
   uint32_t magic_c, magic_s;
   int32_t shift_r, shift_nvp; // same for d = R and d = row_pitch/16 (row tile only)

@@ -570,7 +570,11 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
       T.cfg = ti.tile_cfg; T.split_k = ti.split_k; T.k_steps = ti.k_steps; T.k_steps_per_split = ti.k_steps_per_split;
       T.tiles_m = ti.tiles_m; T.tiles_n = ti.tiles_n;
       T.vec_ok = (d.C % (16 / elem_size(d.in_dtype)) == 0) ? 1 : 0;
-      T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0) ? 1 : 0;
+      // The filter tap of a K step can be found with scalar arithmetic when C is a multiple of the step.  The small tiles
+      // have that form and a per-lane one (conv_tile, STAP): the scalar form pays when the launch puts two workgroups
+      // on most compute units (configs 2 and 3: 8.8 and 14.4 us against 9.4-9.6 and 15.4-15.5), the per-lane form
+      // when a workgroup is alone on its compute unit (config 1 5.7 -> 5.5 us, the late layers of config 5).
+      T.tap_uniform = (d.C % (kTileShapes[ti.tile_cfg].KB / elem_size(d.in_dtype)) == 0 && fused_total > kScalarTapMinItems) ? 1 : 0;
       magic_for(d.C, &T.magic_c, &T.shift_c);
       magic_for(d.S, &T.magic_s, &T.shift_s);
       // the sum of the four partial tiles costs about as much as the LDS reads saved over a few K steps

@@ -440,7 +440,8 @@ _Pragma("unroll")
 // quarter of each K step (sub-step = wavefront index), so every staged byte is read from LDS exactly once.  After
 // the K loop the four partial tiles are summed through LDS, in wavefront order, into the accumulators the
 // pixel/filter division would have produced, and everything downstream (split-K, epilogue) is unchanged.
-template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false, class POL = PlainActs, class TD>
+template <int MT, int NT, int WPX, int WCH, int MF, int KB, int D, int DT, bool GENERIC, bool KW = false, class POL = PlainActs,
+          bool STAP = false, class TD>
 __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr int ES = ElemOf<DT>::ES;
   constexpr int VEC = 16 / ES;          // elements per 16-byte vector
@@ -454,7 +455,6 @@ __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, ch
   constexpr int SUBB = (MF == 32) ? 32 : 64;   // row bytes one MFMA sub-step consumes
   constexpr int NSUB = KB / SUBB;
   static_assert(D % 2 == 0, "D must be even so that register slots and LDS buffers are both static");
-  constexpr bool kOneBlockStep = (MT * NT >= 128 * 64);   // see issue()
   typedef Mma<DT, MF> MMA;
   typedef typename MMA::Acc Acc;
   static_assert(WPX * WCH == 4 && WM % MF == 0 && WN % MF == 0, "bad tile shape");
@@ -523,17 +523,20 @@ __device__ __forceinline__ void conv_tile(const TD& T, const st_work_item it, ch
       const bool kin = k_elem < klimit;
       // filter tap (kr, ksx) and offset of this thread's vector
       int kr, ksx, koff;
-      if (kOneBlockStep || !T.tap_uniform) {
-        // per-lane form.  The large tiles use it always: without a branch the K step is a single basic block,
-        // and the compiler then overlaps the address arithmetic, the loads and the LDS writes with the MFMAs
-        // (a workgroup alone on its compute unit steps 18 % faster)
+      if (!STAP || !T.tap_uniform) {
+        // per-lane form.  Without STAP this is the only form and a K step is a single basic block: the compiler then
+        // overlaps the address arithmetic, the loads and the LDS writes with the MFMAs, which is what a workgroup
+        // alone on its compute unit needs (a 128x128 workgroup steps 18 % faster, config 5's late layers 3 %).
         const int rs = fast_div(k_elem, T.magic_c, T.shift_c);
         kr = fast_div(rs, T.magic_s, T.shift_s);
         ksx = rs - kr * S;
         koff = (kr * W + ksx) * C + (k_elem - rs * C);
       } else {
-        // C is a multiple of the K step: the whole step lies in one filter tap, found with scalar math (the
-        // small tiles have few MFMAs to hide vector arithmetic behind)
+        // C is a multiple of the K step: the whole step lies in one filter tap, found with scalar math.  The small
+        // tiles of a launch that puts two workgroups on most compute units are instantiated with STAP and take this
+        // path (the planner sets tap_uniform for them; the run-time test keeps the step in several basic blocks, and
+        // with a second workgroup to fill the gaps that, with the cheaper arithmetic, is the faster arrangement:
+        // configs 2 and 3 lose 6-8 % with either form as a single block).
         const int rs = fast_div(k_step0, T.magic_c, T.shift_c);
         kr = fast_div(rs, T.magic_s, T.shift_s);
         ksx = rs - kr * S;
@@ -1013,10 +1016,10 @@ __device__ __forceinline__ void conv_tile_rows(const TD& T, const st_work_item i
   }
 }
 
-template <int CFG, int DT, bool GENERIC, bool KW = false, class POL = PlainActs, class TD>
+template <int CFG, int DT, bool GENERIC, bool KW = false, class POL = PlainActs, bool STAP = false, class TD>
 __device__ __forceinline__ void run_cfg(const TD& T, const st_work_item it, char* smem, uint64_t* prof) {
   constexpr TileShape s = kTileShapes[CFG];
-  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW, POL>(T, it, smem, prof);
+  conv_tile<s.MT, s.NT, s.WPX, s.WCH, s.MF, s.KB, s.D, DT, GENERIC, KW, POL, STAP>(T, it, smem, prof);
 }
 
 // TD is TenantDev, or TenantDev qualified with the constant address space (records that no launch in flight
@@ -1028,16 +1031,30 @@ __device__ __forceinline__ void run_dtype(const TD& T, const st_work_item it, ch
       case 0: run_cfg<0, DT, false, false, POL>(T, it, smem, prof); break;
       case 1: run_cfg<1, DT, false, false, POL>(T, it, smem, prof); break;
       case 2: run_cfg<2, DT, false, false, POL>(T, it, smem, prof); break;
-      case 3: run_cfg<3, DT, false, false, POL>(T, it, smem, prof); break;
+      // the three smallest tiles exist with either form of the tap search (see conv_tile)
+      case 3:
+        if (T.tap_uniform) run_cfg<3, DT, false, false, POL, true>(T, it, smem, prof);
+        else run_cfg<3, DT, false, false, POL>(T, it, smem, prof);
+        break;
       // the two smallest tiles split each K step across the wavefronts (see KW above) when the planner found
       // the K loop long enough to repay the final sum of the four partial tiles
       case 4:
-        if (T.k_across_waves) run_cfg<4, DT, false, true, POL>(T, it, smem, prof);
-        else run_cfg<4, DT, false, false, POL>(T, it, smem, prof);
+        if (T.k_across_waves) {
+          if (T.tap_uniform) run_cfg<4, DT, false, true, POL, true>(T, it, smem, prof);
+          else run_cfg<4, DT, false, true, POL>(T, it, smem, prof);
+        } else {
+          if (T.tap_uniform) run_cfg<4, DT, false, false, POL, true>(T, it, smem, prof);
+          else run_cfg<4, DT, false, false, POL>(T, it, smem, prof);
+        }
         break;
       default:
-        if (T.k_across_waves) run_cfg<5, DT, false, true, POL>(T, it, smem, prof);
-        else run_cfg<5, DT, false, false, POL>(T, it, smem, prof);
+        if (T.k_across_waves) {
+          if (T.tap_uniform) run_cfg<5, DT, false, true, POL, true>(T, it, smem, prof);
+          else run_cfg<5, DT, false, true, POL>(T, it, smem, prof);
+        } else {
+          if (T.tap_uniform) run_cfg<5, DT, false, false, POL, true>(T, it, smem, prof);
+          else run_cfg<5, DT, false, false, POL>(T, it, smem, prof);
+        }
         break;
     }
   } else {
