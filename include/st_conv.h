@@ -267,17 +267,18 @@ void st_pipeline_destroy(st_pipeline* pipeline);
  * ops of a sequence, and that sequences share no written tensor.
  *
  * Tiles are chosen per stage (all ops of that stage, over all sequences, planned together as st_conv_plan would).
- * A queue is stage-major, longest work item first within a stage.  There is either one queue for the whole chip,
- * or (the default from 8 sequences on, on a whole 8-XCD device) queues per XCD with sequence s on XCD s mod 8,
- * served only by the workgroups that run on that XCD: a sequence's activations then stay in one XCD's L2, and a
- * finished work item is announced through that L2 (a flag per work item) instead of through memory.  An XCD's
- * entries are split in two queues: the first workgroup to arrive on a compute unit serves the "exclusive" queue,
- * later arrivals the "shared" one, and a stage's entries go to the shared queue only beyond one per compute unit
- * (two tiles sharing a compute unit each run markedly slower than one that has it to itself); a first workgroup
- * whose queue is exhausted goes on with the shared queue.  Activations written during the launch are read with
- * device-scope loads, so no cache is invalidated between stages.
- * Workgroups claim entries in queue order, so the launch needs no guarantee that all of them are resident at once
- * (with queues per XCD: that at least one compute unit of every XCD holds two, eventually); every dependency wait
+ * Within a stage the longest work items come first.  There is either one queue for the whole chip, whose entries
+ * the resident workgroups claim one by one in stage order, or (the default from 8 sequences on, on a whole 8-XCD
+ * device) the work is laid out per XCD, sequence s on XCD s mod 8, served only by the workgroups that run on that
+ * XCD: a sequence's activations then stay in one XCD's L2, and a finished work item is announced through that L2 (a
+ * flag per work item) instead of through memory.  An XCD's entries are dealt into COLUMNS, each a list of entries in
+ * stage order that ONE workgroup works through (it draws its column when it starts; nothing is claimed per entry):
+ * 32 "exclusive" columns, drawn by the first workgroup to arrive on each compute unit, and 32 "shared" ones for later
+ * arrivals; a stage's entries go to the exclusive columns first and to the shared ones only beyond one per compute
+ * unit (two tiles sharing a compute unit each run markedly slower than one that has it to itself).  Activations
+ * written during the launch are read with device-scope loads, so no cache is invalidated between stages.
+ * The one-queue form completes with any number of resident workgroups; the column form needs a workgroup for every
+ * column in use to become resident eventually (on a GPU the launch has to itself all are at once).  Every dependency wait
  * is bounded by a wall-clock limit (default 100 ms) and a poll count, after which the launch abandons the pass:
  * every workgroup leaves, outputs are incomplete, and st_chain_aborted reports it.  Same ops + same inputs =>
  * outputs bitwise identical from run to run, and bitwise identical to running the stages one st_conv_run at a
@@ -302,10 +303,11 @@ typedef struct st_chain_info {
   int64_t flops, bytes;      /* sums over the convolution ops (as st_plan_info)                       */
   int64_t workspace_bytes;   /* split-K partial tiles and counters (shared by a sequence's stages)    */
   int32_t host_only;
-  int32_t n_queues;          /* 1, or 8: queues per XCD                                               */
+  int32_t n_queues;          /* 1, or 8: work laid out per XCD                                        */
+  int32_t columns;           /* columns of each kind per XCD (32), or 0 with one queue               */
   int64_t queue_begin[9];    /* XCD (or the one queue) q owns entries [queue_begin[q], queue_begin[q+1]) */
-  int64_t shared_begin[8];   /* ... of which [queue_begin[q], shared_begin[q]) are its exclusive queue and    */
-                             /* [shared_begin[q], queue_begin[q+1]) its shared queue (empty with one queue)   */
+  int64_t shared_begin[8];   /* ... of which [queue_begin[q], shared_begin[q]) are its exclusive columns and  */
+                             /* [shared_begin[q], queue_begin[q+1]) its shared ones (empty with one queue)    */
 } st_chain_info;
 
 typedef struct st_chain_op_info {
@@ -339,6 +341,10 @@ st_status st_chain_get_op_info(const st_chain* chain, int32_t op, st_chain_op_in
 /* Host copy of the queue, valid until the chain is destroyed; st_work_item.tenant is the op's index in the ops
  * array given to st_chain_plan. */
 st_status st_chain_worklist(const st_chain* chain, const st_work_item** items, int64_t* n_items);
+/* Host copy of the column boundaries, valid until the chain is destroyed: *n = 8 * 2 * columns + 1 (0 with one
+ * queue); column j of XCD x (exclusive: j < columns; shared: columns <= j < 2 * columns) is entries
+ * [begins[x * 2 * columns + j], begins[x * 2 * columns + j + 1]) of the work list. */
+st_status st_chain_columns(const st_chain* chain, const uint32_t** begins, int64_t* n);
 void st_chain_destroy(st_chain* chain);
 
 /* Introspection (used by the bit-exact work-list tests and by reports). */

@@ -25,9 +25,10 @@ struct st_chain {
   uint32_t spin_limit_ticks = 10000000u;     // 100 ms of the 100 MHz constant clock
   uint32_t flags = 0;
   int n_queues = 1;                          // 1, or kNumXCDs
-  // one queue: items[qbegin[0] .. qbegin[1]).  A queue per XCD: XCD x's entries are items[qbegin[2x] .. qbegin[2x + 2]),
-  // the exclusive queue first (2x), then the shared one (2x + 1)
-  uint32_t qbegin[2 * kNumXCDs + 1] = {};
+  // one queue: all of items.  Queues per XCD: column j of XCD x is items[colbegin[x * 2 * kChainColumns + j] ..
+  // colbegin[.. + j + 1]), the kChainColumns exclusive columns first, then the shared ones
+  std::vector<uint32_t> colbegin;
+  uint32_t* d_colbegin = nullptr;
   int workgroups = 0;
   unsigned run_parity = 0;                   // control block the next run uses
   int64_t runs = 0;
@@ -127,7 +128,7 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
     // (a queue per XCD is only used on a whole device: kNumCUs compute units, max_wg / kNumCUs workgroups on each)
     const int cus_per_xcd = kNumCUs / kNumXCDs;
     const bool two_per_cu = max_wg / kNumCUs >= 2;
-    const int n_sub = c->n_queues > 1 ? 2 * kNumXCDs : 1;
+    const int n_sub = c->n_queues > 1 ? kNumXCDs * 2 * kChainColumns : 1;      // columns, or the one queue
     std::vector<std::vector<st_work_item>> queues((size_t)n_sub);
     std::map<int, std::vector<int>> by_stage;          // stage -> op indices, caller's order
     for (int i = 0; i < n_ops; ++i) by_stage[ops[i].stage].push_back(i);
@@ -213,14 +214,14 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
         }
         stage_items[q] += n_it;
       }
-      // one queue: as is.  A queue per XCD: the stage's entries go, one compute unit's worth at a time, alternately
-      // to the XCD's exclusive and shared queue, so a stage with no more entries than compute units never shares one
+      // one queue: as is.  Queues per XCD: the stage's entries (longest first) are dealt to the XCD's columns, to the
+      // exclusive ones first, to the shared ones only beyond one per compute unit, then round again; so a stage with
+      // no more entries than compute units never shares one, and every column is in stage order
       for (int x = 0; x < c->n_queues; ++x) {
         const std::vector<st_work_item>& sq = stage_q[(size_t)x];
-        for (size_t k = 0; k < sq.size(); ++k) {
-          const int cls = (c->n_queues > 1 && two_per_cu) ? (int)((k / (size_t)cus_per_xcd) & 1u) : 0;
-          queues[(size_t)(c->n_queues > 1 ? 2 * x + cls : 0)].push_back(sq[k]);
-        }
+        const size_t ncol = two_per_cu ? 2 * (size_t)kChainColumns : (size_t)kChainColumns;
+        for (size_t k = 0; k < sq.size(); ++k)
+          queues[c->n_queues > 1 ? (size_t)x * 2 * kChainColumns + k % ncol : 0].push_back(sq[k]);
       }
       std::vector<int64_t> cursor((size_t)c->n_sequences, 0), stage_begin((size_t)c->n_sequences, 0);
       for (int q = 0; q < c->n_sequences; ++q) {
@@ -249,14 +250,15 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
       if (total_items >= ((int64_t)1 << 31)) status = fail(ST_ERR_UNSUPPORTED, "more than 2^31 work items");
     }
     if (status == ST_OK) {
+      if (c->n_queues > 1) c->colbegin.assign((size_t)n_sub + 1, 0u);
       for (int qi = 0; qi < n_sub; ++qi) {
-        c->qbegin[qi] = (uint32_t)c->items.size();
+        if (c->n_queues > 1) c->colbegin[(size_t)qi] = (uint32_t)c->items.size();
         c->items.insert(c->items.end(), queues[(size_t)qi].begin(), queues[(size_t)qi].end());
       }
-      for (int qi = n_sub; qi <= 2 * kNumXCDs; ++qi) c->qbegin[qi] = (uint32_t)c->items.size();
+      if (c->n_queues > 1) c->colbegin[(size_t)n_sub] = (uint32_t)c->items.size();
     }
     if (status == ST_OK) {
-      // arena: [op table][queue][control block x2][split-K counters][completion flags][split-K partial tiles]
+      // arena: [op table][queue][control block x2][split-K counters][completion flags][column boundaries][split-K partial tiles]
       auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
       c->ctl_slots = (uint32_t)(kChainCtlSeq + c->n_sequences);
       int64_t ws_total = 0, ct_total = 0;
@@ -271,7 +273,8 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
       const size_t ctl_words = (size_t)c->ctl_slots * kChainCtlStride + kChainRankWords;   // one control block
       const size_t off_ct = off_ctl + up(ctl_words * 4 * 2);
       const size_t off_flags = off_ct + up((size_t)ct_total * 4);
-      const size_t off_ws = off_flags + up(c->n_queues > 1 ? c->items.size() * 4 : 0);
+      const size_t off_cols = off_flags + up(c->n_queues > 1 ? c->items.size() * 4 : 0);
+      const size_t off_ws = off_cols + up(c->colbegin.size() * 4);
       const size_t total = off_ws + (size_t)ws_total * 4;
       if (!host_only && n_ops > 0) {
         hipError_t e = hipMalloc((void**)&c->d_arena, total);
@@ -285,6 +288,7 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
           std::vector<char> host(off_ws, 0);
           std::memcpy(host.data(), c->table.data(), (size_t)n_ops * sizeof(TenantDev));
           std::memcpy(host.data() + off_items, c->items.data(), c->items.size() * sizeof(st_work_item));
+          if (!c->colbegin.empty()) std::memcpy(host.data() + off_cols, c->colbegin.data(), c->colbegin.size() * 4);
           e = hipMemcpy(c->d_arena, host.data(), off_ws, hipMemcpyHostToDevice);
           if (e != hipSuccess) status = hip_fail(e, "hipMemcpy (chain tables)");
           c->d_ops = (TenantDev*)c->d_arena;
@@ -296,11 +300,12 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
           if (c->n_queues > 1) {
             c->d_item_flags = (uint32_t*)(c->d_arena + off_flags);
             c->item_flags_bytes = c->items.size() * 4;
+            c->d_colbegin = (uint32_t*)(c->d_arena + off_cols);
           }
         }
       }
-      // one queue: no more workgroups than entries; a queue per XCD: every resident slot (workgroup b runs on XCD
-      // b mod 8, and a queue with fewer entries than its XCD has slots just sends the surplus home at once)
+      // one queue: no more workgroups than entries; queues per XCD: every resident slot (a workgroup for which no column
+      // is left goes home at once)
       c->workgroups = c->n_queues > 1 ? max_wg : (int)std::min<int64_t>((int64_t)c->items.size(), max_wg);
     }
   } catch (const std::bad_alloc&) {
@@ -325,8 +330,9 @@ static st_status chain_launch(st_chain* c, void* stream, uint64_t* prof_dev) {
     if (c->d_item_flags) ST_HIP((hipError_t)launch_zero(c->d_item_flags, (int64_t)((c->item_flags_bytes + 15) & ~(size_t)15), stream));
     c->run_number = 1u;
   }
-  ST_HIP((hipError_t)launch_chain(c->d_ops, c->d_items, c->qbegin, (uint32_t)c->n_queues, c->d_ctl[p], c->d_ctl[p ^ 1u], c->ctl_slots,
-                                  c->d_item_flags, c->run_number, c->spin_limit_ticks, c->flags, c->workgroups, stream, prof_dev));
+  ST_HIP((hipError_t)launch_chain(c->d_ops, c->d_items, (uint32_t)c->items.size(), c->d_colbegin, (uint32_t)c->n_queues, c->d_ctl[p],
+                                  c->d_ctl[p ^ 1u], c->ctl_slots, c->d_item_flags, c->run_number, c->spin_limit_ticks, c->flags,
+                                  c->workgroups, stream, prof_dev));
   c->run_parity = p ^ 1u;
   ++c->runs;
   return ST_OK;
@@ -394,8 +400,12 @@ extern "C" st_status st_chain_get_info(const st_chain* chain, st_chain_info* out
   out->workspace_bytes = chain->workspace_bytes;
   out->host_only = chain->host_only ? 1 : 0;
   out->n_queues = chain->n_queues;
-  for (int q = 0; q <= kNumXCDs; ++q) out->queue_begin[q] = chain->qbegin[chain->n_queues > 1 ? 2 * q : std::min(q, 1)];
-  for (int q = 0; q < kNumXCDs; ++q) out->shared_begin[q] = chain->n_queues > 1 ? chain->qbegin[2 * q + 1] : out->queue_begin[q + 1];
+  const int64_t n = (int64_t)chain->items.size();
+  for (int q = 0; q <= kNumXCDs; ++q)
+    out->queue_begin[q] = chain->n_queues > 1 ? chain->colbegin[(size_t)q * 2 * kChainColumns] : (q == 0 ? 0 : n);
+  for (int q = 0; q < kNumXCDs; ++q)
+    out->shared_begin[q] = chain->n_queues > 1 ? chain->colbegin[(size_t)q * 2 * kChainColumns + kChainColumns] : out->queue_begin[q + 1];
+  out->columns = chain->n_queues > 1 ? kChainColumns : 0;
   return ST_OK;
 }
 
@@ -410,6 +420,13 @@ extern "C" st_status st_chain_worklist(const st_chain* chain, const st_work_item
   if (!chain || !items || !n_items) return fail(ST_ERR_INVALID_ARG, "NULL argument");
   *items = chain->items.data();
   *n_items = (int64_t)chain->items.size();
+  return ST_OK;
+}
+
+extern "C" st_status st_chain_columns(const st_chain* chain, const uint32_t** begins, int64_t* n) {
+  if (!chain || !begins || !n) return fail(ST_ERR_INVALID_ARG, "NULL argument");
+  *begins = chain->colbegin.empty() ? nullptr : chain->colbegin.data();
+  *n = (int64_t)chain->colbegin.size();
   return ST_OK;
 }
 

@@ -42,10 +42,13 @@ struct ChainArgs {
   uint32_t ctl_slots;     // 256-byte slots of a control block (one live word each); kChainRankWords dense words follow them
   uint32_t spin_limit;    // ticks of the 100 MHz constant clock a dependency wait may last
   uint32_t flags;         // kChainFlag*
-  uint32_t n_queues;      // 1: one queue for the whole chip; kNumXCDs: two queues per XCD (see st_chain_kernel)
-  uint32_t qbegin[2 * kNumXCDs + 1];   // queue j is items[qbegin[j] .. qbegin[j + 1]); with one queue only j = 0 is used
+  uint32_t n_queues;      // 1: one queue for the whole chip, entries claimed one by one; kNumXCDs: columns (see st_chain_kernel)
+  uint32_t q_end;         // one queue: it is items[0 .. q_end)
+  const uint32_t* colbegin;   // columns: column j of XCD x is items[colbegin[x * 2 * kChainColumns + j] .. colbegin[.. + j + 1])
 };
 
+constexpr int kChainGraceLooks = 12;             // looks at a dependency (0.3 us each) before the filter touches are issued
+                                                 // (measured per pass of the 8 x 53-layer chain: 3 looks 495 us, 6: 487, 12: 482, 30: 484, never touching: 494)
 constexpr uint32_t kChainMaxPolls = 1u << 22;   // a poll takes a microsecond or so: seconds, far beyond any real wait
 
 // The op table and the queue never change while a launch runs: they are read through the constant address space, so
@@ -118,13 +121,17 @@ __device__ __forceinline__ uint32_t chain_claim(const ChainArgs& a, uint32_t q, 
   return idx;
 }
 
-// With one queue per XCD, the XCD's entries are split in two: queue 2x ("exclusive") and queue 2x + 1 ("shared").  Two
+// With queues per XCD, an XCD's entries are dealt into 2 x kChainColumns COLUMNS, each a list of entries in stage
+// order, and every workgroup works through ONE column that it draws when it starts (one atomic): nothing is claimed
+// per entry, so no round trip to memory stands between a finished entry and the workgroup's next one.  Two
 // workgroups fit a compute unit, and two tiles that share one run 20-45 % slower each than a tile that has it to
 // itself; a stage of a sequence often has no more tiles than the XCD has compute units.  So the first workgroup to
-// arrive on a compute unit serves the exclusive queue and every later one the shared queue, and the host puts a
-// stage's entries into the shared queue only beyond one per compute unit.  A first workgroup whose queue is exhausted
-// goes on with the shared queue; should no second workgroup become resident on the whole XCD within the wait limit
-// while shared entries are due, the pass is abandoned and reported like any other expired wait.
+// arrive on a compute unit draws one of the kChainColumns EXCLUSIVE columns and every later one a SHARED column, and
+// the host deals a stage's entries (longest first) to the exclusive columns first, to the shared ones only beyond
+// one per compute unit.  Every column that holds entries needs a workgroup: should fewer become resident on an XCD
+// than it has columns in use, the entries of the columns nobody drew stay undone, their dependants' waits expire,
+// and the pass is abandoned and reported.  (The one-queue form, whose entries are claimed one by one, completes with
+// any number of resident workgroups.)
 __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[kSmemBytes];
   __shared__ uint32_t s_msg[2];
@@ -136,12 +143,13 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
     for (uint32_t i = (uint32_t)tid; i < (uint32_t)kChainRankWords; i += kThreads)
       __hip_atomic_store(&a.ctl_other[a.ctl_slots * kChainCtlStride + i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  // which queues this workgroup serves, in which order
-  uint32_t q_first = 0u, n_serve = 1u;
-  if (a.n_queues > 1u) {
+  // the entries of this workgroup: [qb, qe) of the work list; one queue: claimed one by one from all of it
+  const bool claiming = a.n_queues == 1u;
+  uint32_t qb = 0u, qe = a.q_end;
+  if (!claiming) {
     const uint32_t xcc = (uint32_t)__builtin_amdgcn_s_getreg(0x1814) & 15u;       // XCC_ID
     if (xcc >= a.n_queues) {
-      // an XCD this launch was not planned for: its workgroups must not touch any queue (completion flags are only
+      // an XCD this launch was not planned for: its workgroups must not touch any entry (completion flags are only
       // valid inside one XCD); the pass is reported as abandoned
       if (tid == 0) __hip_atomic_store(&a.ctl[kChainCtlAbort * kChainCtlStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
@@ -149,27 +157,30 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
     if (tid == 0) {
       // shader engine, shader array and compute unit of HW_ID: one of kChainRankWords / kNumXCDs keys per XCD
       const uint32_t cu = ((uint32_t)__builtin_amdgcn_s_getreg(0xF804) >> 8) & 255u;
-      s_msg[0] = __hip_atomic_fetch_add(&a.ctl[a.ctl_slots * kChainCtlStride + xcc * 256u + cu], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t arrived = __hip_atomic_fetch_add(&a.ctl[a.ctl_slots * kChainCtlStride + xcc * 256u + cu], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t cls = arrived != 0u ? 1u : 0u;
+      const uint32_t drawn = __hip_atomic_fetch_add(&a.ctl[(kChainCtlHead + 2u * xcc + cls) * kChainCtlStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_msg[0] = drawn < (uint32_t)kChainColumns ? xcc * 2u * kChainColumns + cls * kChainColumns + drawn : 0xffffffffu;
     }
     __syncthreads();
-    const uint32_t arrived = __builtin_amdgcn_readfirstlane(s_msg[0]);
+    const uint32_t col = __builtin_amdgcn_readfirstlane(s_msg[0]);
     __syncthreads();
-    q_first = 2u * xcc + (arrived != 0u ? 1u : 0u);
-    // only the first workgroup of a compute unit goes on to the other queue (a later one would bring back the
-    // sharing that the exclusive queue avoids)
-    n_serve = arrived != 0u ? 1u : 2u;
+    if (col == 0xffffffffu) return;        // every column of this kind has its workgroup
+    const __attribute__((address_space(4))) uint32_t* cb = (const __attribute__((address_space(4))) uint32_t*)(a.colbegin + col);
+    qb = cb[0];
+    qe = cb[1];
   }
   uint32_t n_done = 0u;
-  bool left = false;
-  for (uint32_t serve = 0; serve < n_serve && !left; ++serve) {
-    const uint32_t q = q_first ^ serve;
-    const uint32_t qb = a.qbegin[q], qe = a.qbegin[q + 1];
-    uint32_t next = 0xffffffffu;            // thread 0: the entry claimed ahead
-    if (tid == 0) next = chain_claim(a, q, qb, qe);
+  {
+    uint32_t next = 0xffffffffu;            // one queue, thread 0: the entry claimed ahead
+    if (claiming && tid == 0) next = chain_claim(a, 0u, qb, qe);
     for (uint32_t round = 0; round <= qe - qb; ++round) {
-      if (tid == 0) s_msg[0] = next;
-      __syncthreads();
-      const uint32_t idx = __builtin_amdgcn_readfirstlane(s_msg[0]);
+      uint32_t idx = qb + round;
+      if (claiming) {
+        if (tid == 0) s_msg[0] = next;
+        __syncthreads();
+        idx = __builtin_amdgcn_readfirstlane(s_msg[0]);
+      }
       if (idx >= qe) break;
       ConstItem* ip = (ConstItem*)(a.items + idx);
       st_work_item it;
@@ -202,16 +213,22 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
           }
           return true;
         };
-        // first look: an entry whose dependency is already complete starts at once
+        // first looks: an entry whose dependency is complete, or completes within a couple of microseconds (the
+        // workgroups of a stage finish within about one of each other), starts at once
         if (tid < 64) {
-          const bool ready = satisfied();
+          bool ready = satisfied();
+          for (int g = 0; g < kChainGraceLooks && !ready; ++g) {
+            __builtin_amdgcn_s_sleep(2);
+            ready = satisfied();
+          }
           if (tid == 0) s_msg[1] = ready ? 1u : 2u;
         }
         __syncthreads();
         const uint32_t first = s_msg[1];
         if (first == 2u) {
           __syncthreads();                    // s_msg[1] has been read by everyone
-          // not yet: pull the filter slab closer while waiting
+          // a longer wait: pull the filter slab closer meanwhile (the touches must have returned before the entry
+          // starts, which is why an entry that is about to become ready does not issue them)
           const uint32_t touched = prefetch_filters(T, it, tid);
           if (tid < 64) {
             const uint64_t t0 = wall_clock64();
@@ -234,7 +251,7 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
           // split-K partial tiles) is read with device-scope loads, and everything else did not change.
           __syncthreads();
           asm volatile("" ::"v"(touched));      // the prefetch loads are complete (and not optimised away)
-          if (s_msg[1] == 0u) { left = true; break; }
+          if (s_msg[1] == 0u) break;
         }
       }
       if (T.cfg == kChainPoolCfg && prof && tid == 0) prof[4] = wall_clock64();
@@ -252,10 +269,10 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
         } else {
           __hip_atomic_fetch_add(a.ctl + (kChainCtlSeq + T.chain_seq) * kChainCtlStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // The following entry is claimed only now.  The claim is a round trip to memory: issued before the entry's
-        // work it sits in front of the first operand loads in the in-order memory counter; issued before the
+        // One queue: the following entry is claimed only now.  The claim is a round trip to memory: issued before the
+        // entry's work it sits in front of the first operand loads in the in-order memory counter; issued before the
         // completion signal (even as early as the end of the K loop: measured) it delays every dependant.
-        next = chain_claim(a, q, qb, qe);
+        if (claiming) next = chain_claim(a, 0u, qb, qe);
         if (prof) {
           prof[7] = waited;
           if (T.cfg == kChainPoolCfg) prof[6] = wall_clock64();
@@ -282,14 +299,13 @@ int chain_max_workgroups(int* out_workgroups, int* out_xcds) {
   return 0;
 }
 
-int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const uint32_t* qbegin, uint32_t n_queues, uint32_t* ctl,
-                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number, uint32_t spin_limit_ticks,
-                 uint32_t flags, int grid, void* stream, uint64_t* prof_dev) {
+int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, uint32_t n_items, const uint32_t* colbegin_dev, uint32_t n_queues,
+                 uint32_t* ctl, uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number,
+                 uint32_t spin_limit_ticks, uint32_t flags, int grid, void* stream, uint64_t* prof_dev) {
   if (n_queues != 1u && n_queues != (uint32_t)kNumXCDs) return (int)hipErrorInvalidValue;
-  const uint32_t n_sub = n_queues == 1u ? 1u : 2u * n_queues;
-  if (grid <= 0 || qbegin[n_sub] == 0u) return 0;
+  if (grid <= 0 || n_items == 0u) return 0;
   if (((flags & kChainFlagLocalFlags) != 0u) != (n_queues > 1u)) return (int)hipErrorInvalidValue;
-  if ((flags & kChainFlagLocalFlags) != 0u && (item_flags == nullptr || run_number == 0u)) return (int)hipErrorInvalidValue;
+  if (n_queues > 1u && (item_flags == nullptr || run_number == 0u || colbegin_dev == nullptr)) return (int)hipErrorInvalidValue;
   ChainArgs a;
   a.ops = ops_dev;
   a.items = items_dev;
@@ -302,7 +318,8 @@ int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const 
   a.spin_limit = spin_limit_ticks;
   a.flags = flags;
   a.n_queues = n_queues;
-  for (uint32_t j = 0; j <= 2u * kNumXCDs; ++j) a.qbegin[j] = qbegin[j <= n_sub ? j : n_sub];
+  a.q_end = n_items;
+  a.colbegin = colbegin_dev;
   hipLaunchKernelGGL(st_chain_kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }

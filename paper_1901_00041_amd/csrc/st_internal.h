@@ -84,19 +84,22 @@ int launch_conv(const TenantDev* tenants_dev, const st_work_item* items_dev, int
 // Persistent chain launch (st_chain.hip).  ctl / ctl_other: this run's and the next run's control block.  A block is
 // ctl_slots slots of kChainCtlStride 32-bit words (256 bytes) with one live word each, so that the words hundreds of
 // workgroups poll and bump sit in different cache lines and memory channels: slot kChainCtlAbort the abort flag,
-// kChainCtlDone the count of completed work items, kChainCtlHead + j the head of queue j, kChainCtlSeq + s the
-// completion counter of sequence s; kChainRankWords dense words follow the slots (how many workgroups have arrived
-// on each compute unit).  n_queues is 1 or kNumXCDs; qbegin (host array) holds the boundaries of the one queue, or of
-// the 2 * kNumXCDs queues (XCD x: exclusive queue 2x, shared queue 2x + 1).  item_flags / run_number:
-// the per-item completion flags and this run's number (kChainFlagLocalFlags only; else nullptr / anything).
+// kChainCtlDone the count of completed work items, kChainCtlHead the head of the one queue, or with queues per XCD
+// kChainCtlHead + 2x + k the number of exclusive (k = 0) / shared (k = 1) columns of XCD x drawn so far,
+// kChainCtlSeq + s the completion counter of sequence s; kChainRankWords dense words follow the slots (how many
+// workgroups have arrived on each compute unit).  n_queues is 1 (entries [0, n_items) claimed one by one) or
+// kNumXCDs (colbegin_dev: kNumXCDs * 2 * kChainColumns + 1 column boundaries in device memory; XCD x's exclusive
+// columns are x * 2 * kChainColumns + [0, kChainColumns), its shared ones follow).  item_flags / run_number: the
+// per-item completion flags and this run's number (queues per XCD only; else nullptr / anything).
 constexpr int kChainCtlStride = 64;
 constexpr int kChainCtlAbort = 1, kChainCtlDone = 2, kChainCtlHead = 4, kChainCtlSeq = 4 + 2 * kNumXCDs;
 constexpr int kChainRankWords = kNumXCDs * 256;   // arrival counts per (XCD, compute unit key), dense, after the slots
+constexpr int kChainColumns = kNumCUs / kNumXCDs; // exclusive columns per XCD (one per compute unit), and as many shared
 constexpr uint32_t kChainFlagLocalFlags = 4u;     // completion travels through per-item flags in the XCD's own L2
 int chain_max_workgroups(int* out_workgroups, int* out_xcds);
-int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, const uint32_t* qbegin, uint32_t n_queues, uint32_t* ctl,
-                 uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number, uint32_t spin_limit_ticks,
-                 uint32_t flags, int grid, void* stream, uint64_t* prof_dev);
+int launch_chain(const TenantDev* ops_dev, const st_work_item* items_dev, uint32_t n_items, const uint32_t* colbegin_dev, uint32_t n_queues,
+                 uint32_t* ctl, uint32_t* ctl_other, uint32_t ctl_slots, uint32_t* item_flags, uint32_t run_number,
+                 uint32_t spin_limit_ticks, uint32_t flags, int grid, void* stream, uint64_t* prof_dev);
 int launch_empty(void* stream);
 // Allocation-free path: device address of the current GPU's fixed scratch array (looked up on first use per device),
 // host bytes -> device through kernel arguments (sizes rounded up to 16 bytes; dst 16-byte aligned), and a zero fill.

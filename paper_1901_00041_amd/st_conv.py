@@ -24,7 +24,7 @@ EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_noalloc", "st_conv_noallo
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
-           "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
+           "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns", "st_chain_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
 
@@ -75,7 +75,7 @@ class st_chain_info(ctypes.Structure):
     _fields_ = [("n_ops", ctypes.c_int32), ("n_sequences", ctypes.c_int32), ("n_stages", ctypes.c_int32),
                 ("workgroups", ctypes.c_int32), ("n_items", ctypes.c_int64), ("flops", ctypes.c_int64),
                 ("bytes", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64), ("host_only", ctypes.c_int32),
-                ("n_queues", ctypes.c_int32), ("queue_begin", ctypes.c_int64 * 9),
+                ("n_queues", ctypes.c_int32), ("columns", ctypes.c_int32), ("queue_begin", ctypes.c_int64 * 9),
                 ("shared_begin", ctypes.c_int64 * 8)]
 
 
@@ -160,10 +160,11 @@ def lib() -> ctypes.CDLL:
         L.st_chain_get_info.argtypes = [vp, P(st_chain_info)]
         L.st_chain_get_op_info.argtypes = [vp, i32, P(st_chain_op_info)]
         L.st_chain_worklist.argtypes = [vp, P(P(st_work_item)), P(i64)]
+        L.st_chain_columns.argtypes = [vp, P(P(ctypes.c_uint32)), P(i64)]
         L.st_chain_destroy.argtypes = [vp]
         L.st_chain_destroy.restype = None
         for name in ("st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
-                     "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist"):
+                     "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns"):
             getattr(L, name).restype = i32
         L.st_tile_shape.argtypes = [i32, P(i32), P(i32), P(i32)]
         L.st_tile_count.argtypes = []
@@ -474,6 +475,15 @@ class Chain:
         if n.value == 0:
             return np.zeros(0, dtype=WORK_ITEM_DTYPE)
         return np.frombuffer(ctypes.string_at(p, n.value * ctypes.sizeof(st_work_item)), dtype=WORK_ITEM_DTYPE).copy()
+
+    def columns(self) -> np.ndarray:
+        """Column boundaries (8 * 2 * info().columns + 1 entries; empty with one queue), see st_chain_columns."""
+        p = ctypes.POINTER(ctypes.c_uint32)()
+        n = ctypes.c_int64()
+        _check(lib().st_chain_columns(self.handle, ctypes.byref(p), ctypes.byref(n)), "st_chain_columns")
+        if n.value == 0:
+            return np.zeros(0, dtype=np.uint32)
+        return np.frombuffer(ctypes.string_at(p, n.value * 4), dtype=np.uint32).copy()
 
     def destroy(self):
         if getattr(self, "handle", None) and _lib is not None:

@@ -57,36 +57,40 @@ def _check_chain(ops, chain):
             assert got == want and len(mine) == len(want), i
         else:
             assert sorted(mine["tile_m"].tolist()) == list(range(oi.item_count)) and (mine["tile_n"] == 0).all()
-    # an XCD's entries (or the one queue's) hold whole sequences (sequence s on XCD s mod n_queues); its exclusive and
-    # its shared queue are each stage-major; a stage's entries go to the shared queue only beyond one per compute
-    # unit (32 per XCD), 32 at a time alternately
+    # an XCD's entries (or the one queue's) hold whole sequences (sequence s on XCD s mod n_queues).  One queue: stage
+    # order.  Per XCD: 32 exclusive + 32 shared columns, each in stage order; a stage's entries are dealt to the columns
+    # in turn, exclusive ones first, so its k-th entry sits in column k mod 64 and a stage of at most 32 entries never
+    # touches a shared column
     qb = list(info.queue_begin)[:info.n_queues + 1]
     sb = list(info.shared_begin)[:info.n_queues]
+    cols = chain.columns()
     assert qb[0] == 0 and qb[-1] == len(items) and info.n_queues in (1, 8)
-    for q in range(info.n_queues):
-        assert qb[q] <= sb[q] <= qb[q + 1]
-        if info.n_queues == 1:
-            assert sb[q] == qb[q + 1]
-        excl, shared = items["tenant"][qb[q]:sb[q]], items["tenant"][sb[q]:qb[q + 1]]
-        for seg in (excl, shared):
-            assert (np.diff(np.array([ops[t].stage for t in seg])) >= 0).all()
-            assert all(ops[t].sequence % info.n_queues == q for t in seg)
-        if info.n_queues > 1:
-            n_e = {st: 0 for st in {o.stage for o in ops}}
-            n_s = dict(n_e)
-            for t in excl:
-                n_e[ops[t].stage] += 1
-            for t in shared:
-                n_s[ops[t].stage] += 1
-            for st in n_e:
-                n = n_e[st] + n_s[st]
-                assert n_e[st] == sum(min(32, max(0, n - 64 * r)) for r in range(n // 64 + 1)), (q, st, n, n_e[st])
+    stage_of = np.array([ops[t].stage for t in items["tenant"]])
+    if info.n_queues == 1:
+        assert info.columns == 0 and len(cols) == 0 and sb[0] == qb[1]
+        assert (np.diff(stage_of) >= 0).all()
+    else:
+        nc = info.columns
+        assert nc == 32 and len(cols) == 8 * 2 * nc + 1 and cols[0] == 0 and cols[-1] == len(items) and (np.diff(cols.astype(np.int64)) >= 0).all()
+        for q in range(8):
+            assert qb[q] == cols[q * 2 * nc] and sb[q] == cols[q * 2 * nc + nc]
+            assert all(ops[t].sequence % 8 == q for t in items["tenant"][qb[q]:qb[q + 1]])
+            per_stage = {}
+            for j in range(2 * nc):
+                lo, hi = int(cols[q * 2 * nc + j]), int(cols[q * 2 * nc + j + 1])
+                assert (np.diff(stage_of[lo:hi]) >= 0).all()
+                for st in stage_of[lo:hi]:
+                    per_stage.setdefault(int(st), [0] * (2 * nc))[j] += 1
+            for st, cnt in per_stage.items():
+                n = sum(cnt)
+                assert cnt == [n // (2 * nc) + (1 if j < n % (2 * nc) else 0) for j in range(2 * nc)], (q, st, cnt)
     # thresholds: items of the op's sequence in strictly earlier stages
     for i, oi in enumerate(per_op):
         need = sum(p.item_count for j, p in enumerate(per_op) if p.sequence == oi.sequence and p.stage < oi.stage)
         assert oi.need == need, (i, oi.need, need)
-    # progress: an entry waits only for entries of strictly earlier stages (the thresholds above), and every queue is
-    # stage-major and claimed in order, so the unfinished entry of the lowest stage is always claimable
+    # progress: an entry waits only for entries of strictly earlier stages (the thresholds above); the one queue is
+    # claimed in stage order and every column is worked through in stage order, so an unfinished entry of the lowest
+    # unfinished stage is never behind an entry that waits
     return per_op
 
 
