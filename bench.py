@@ -38,7 +38,7 @@ PEAK_F32_TFLOPS = 157.3       # MI355X fp32 matrix
 PEAK_HBM_GBS = 8000.0
 HEADLINE_CONFIG = 5           # configs[4]: the largest single-GPU configuration
 # passes per step: a step lasts 10-20 ms for the fused policy
-PASSES_PER_STEP = {1: 2048, 2: 2048, 3: 1024, 4: 256, 5: 32}
+PASSES_PER_STEP = {1: 2048, 2: 2048, 3: 1024, 4: 256, 5: 40}
 # the form of the fused policy that `value` reports, per configuration (fixed; every other form is an extra):
 # one fused launch per pass for the single-layer configurations, and for the 53-layer stacks one persistent launch
 # per pass (the layer-by-layer form, 49 fused launches per pass, is timed beside it as "fused")
