@@ -77,8 +77,8 @@ typedef struct st_plan_opts {
   int32_t target_items;  /* 0 = default; else the workgroup slots the planner's cost model fills      */
   int32_t rows_per_tile; /* 0 = choose; 1, 2 or 4 forces the output rows per work item of row-tiled   */
                          /* tenants (ignored for the others)                                         */
-  int32_t chain_queues;  /* st_chain_plan only: 0 = choose; 1 = one work queue for the whole chip; 2 = one  */
-                         /* queue per XCD, each sequence bound to one XCD (needs a whole 8-XCD device)      */
+  int32_t chain_queues;  /* st_chain_plan only: 0 = choose; 1 = one work queue for the whole chip; 2 = the  */
+                         /* per-XCD layout, each sequence bound to one XCD (needs a whole 8-XCD device)     */
   int32_t reserved;      /* must be 0                                                                */
 } st_plan_opts;
 

@@ -109,8 +109,8 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
     c->info.resize(n_ops);
     c->table.resize(n_ops);
     c->n_sequences = max_seq + 1;
-    // One queue per XCD when every XCD gets at least one sequence (and the device is a whole 8-XCD one); else one
-    // queue for the chip.  A host-only chain is laid out for a whole device.
+    // The work is laid out per XCD when every XCD gets at least one sequence (and the device is a whole 8-XCD one);
+    // else there is one queue for the chip.  A host-only chain is laid out for a whole device.
     int max_wg = 2 * kNumCUs, n_xcd = kNumXCDs;
     if (!host_only && n_ops > 0) {
       const hipError_t e = (hipError_t)chain_max_workgroups(&max_wg, &n_xcd);
@@ -118,15 +118,13 @@ extern "C" st_status st_chain_plan(const st_chain_op* ops, int32_t n_ops, const 
     }
     if (want_queues == 2 && n_xcd != kNumXCDs) {
       delete c;
-      return fail(ST_ERR_UNSUPPORTED, "one queue per XCD needs a device with %d XCDs, this one shows %d", kNumXCDs, n_xcd);
+      return fail(ST_ERR_UNSUPPORTED, "the per-XCD layout needs a device with %d XCDs, this one shows %d", kNumXCDs, n_xcd);
     }
     c->n_queues = (want_queues == 2 || (want_queues == 0 && n_xcd == kNumXCDs && c->n_sequences >= kNumXCDs)) ? kNumXCDs : 1;
-    // a queue per XCD: producer and consumer of a sequence share that XCD's L2, and completion travels through it
+    // per XCD: producer and consumer of a sequence share that XCD's L2, and completion travels through it
     c->flags = c->n_queues > 1 ? kChainFlagLocalFlags : 0u;
-    // compute units per XCD and workgroups that fit one: a stage's entries go to an XCD's shared queue only beyond
-    // one per compute unit (and never when a compute unit holds one workgroup only)
-    // (a queue per XCD is only used on a whole device: kNumCUs compute units, max_wg / kNumCUs workgroups on each)
-    const int cus_per_xcd = kNumCUs / kNumXCDs;
+    // The shared columns are only used when a compute unit holds two workgroups (the per-XCD layout exists on a whole
+    // device only: kNumCUs compute units, max_wg / kNumCUs workgroups on each).
     const bool two_per_cu = max_wg / kNumCUs >= 2;
     const int n_sub = c->n_queues > 1 ? kNumXCDs * 2 * kChainColumns : 1;      // columns, or the one queue
     std::vector<std::vector<st_work_item>> queues((size_t)n_sub);
