@@ -92,6 +92,8 @@ static const double kGenericFirstCost = 19000.0;
 static const double kSplitCost = 5000.0, kSplitPerElem = 1.0, kSplitRoundCost = 2700.0;   // hand-off grows with the tile
 static const int kSlots = 400;                  // two workgroups resident per compute unit (512), derated because
                                                 // co-resident workgroups share one LDS pipe
+static const double kAloneFactor = 0.77;        // item time of a workgroup that has its compute unit to itself (two that
+                                                // share one each run 20-45 % slower)
 static const int kKAcrossWavesMinSteps = 6;     // shortest K loop for which the 32x64 and 16x64 tiles split K across wavefronts
 static const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
 
@@ -314,6 +316,16 @@ static void choose_all(const std::vector<std::vector<Option>>& opts, int slots, 
   }
 }
 
+// The model's duration of a launch with the given choice per tenant.
+static double modelled(const std::vector<std::vector<Option>>& opts, const std::vector<int>& pick, int slots) {
+  double longest = 0.0, area = 0.0;
+  for (size_t t = 0; t < opts.size(); ++t) {
+    longest = std::max(longest, opts[t][pick[t]].item_time);
+    area += opts[t][pick[t]].area;
+  }
+  return std::max(longest, area / slots);
+}
+
 static void destroy_device(st_plan* p) {
   if (p->d_arena) (void)hipFree(p->d_arena);
   p->d_arena = nullptr;
@@ -447,6 +459,16 @@ extern "C" st_status st_conv_plan(const st_conv_desc* descs, int32_t n_tenants, 
     }
     std::vector<int> pick;
     choose_all(options, o.target_items > 0 ? o.target_items : kSlots, &pick);
+    if (o.target_items == 0) {
+      // A launch of no more work items than compute units puts every workgroup on a compute unit of its own, where
+      // it runs faster than beside a second one (kAloneFactor).  Plan for that too, and take it if the model says
+      // it is the shorter launch (config 3: 224 tiles of 64x64 in 13.3 us against 416 of 32x64 in 14.5).
+      std::vector<int> alone;
+      choose_all(options, kNumCUs, &alone);
+      int64_t n_alone = 0;
+      for (int t = 0; t < n_tenants; ++t) n_alone += options[t][alone[t]].items;
+      if (n_alone <= kNumCUs && kAloneFactor * modelled(options, alone, kNumCUs) < modelled(options, pick, kSlots)) pick = alone;
+    }
     int64_t fused_total = 0;
     for (int t = 0; t < n_tenants; ++t) {
       st_tenant_info& ti = p->info[t];
