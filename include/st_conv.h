@@ -278,7 +278,9 @@ void st_pipeline_destroy(st_pipeline* pipeline);
  * unit (two tiles sharing a compute unit each run markedly slower than one that has it to itself).  Activations
  * written during the launch are read with device-scope loads, so no cache is invalidated between stages.
  * The one-queue form completes with any number of resident workgroups; the column form needs a workgroup for every
- * column in use to become resident eventually (on a GPU the launch has to itself all are at once).  Every dependency wait
+ * column in use to become resident eventually (on a GPU the launch has to itself all are at once; a caller that shares
+ * the GPU with long-running kernels of its own and sees passes abandoned should plan with chain_queues = 1).  Every
+ * dependency wait
  * is bounded by a wall-clock limit (default 100 ms) and a poll count, after which the launch abandons the pass:
  * every workgroup leaves, outputs are incomplete, and st_chain_aborted reports it.  Same ops + same inputs =>
  * outputs bitwise identical from run to run, and bitwise identical to running the stages one st_conv_run at a
@@ -336,6 +338,10 @@ st_status st_chain_aborted(st_chain* chain, int32_t* aborted);
 /* The wall-clock limit of a dependency wait in microseconds (0 = give up at once unless already satisfied: a test
  * hook that makes every kernel still exit normally). */
 st_status st_chain_set_wait_limit_us(st_chain* chain, int64_t microseconds);
+/* Size of the launch in workgroups (0 = the planned size, st_chain_info.workgroups; at most that).  A test hook
+ * too: with fewer workgroups than the column form needs, the undrawn columns' dependants give up after the wait
+ * limit and the pass is reported as abandoned, every kernel still exiting normally. */
+st_status st_chain_set_workgroups(st_chain* chain, int32_t workgroups);
 st_status st_chain_get_info(const st_chain* chain, st_chain_info* out);
 st_status st_chain_get_op_info(const st_chain* chain, int32_t op, st_chain_op_info* out);
 /* Host copy of the queue, valid until the chain is destroyed; st_work_item.tenant is the op's index in the ops

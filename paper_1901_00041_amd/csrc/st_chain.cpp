@@ -29,7 +29,8 @@ struct st_chain {
   // colbegin[.. + j + 1]), the kChainColumns exclusive columns first, then the shared ones
   std::vector<uint32_t> colbegin;
   uint32_t* d_colbegin = nullptr;
-  int workgroups = 0;
+  int workgroups = 0;                        // planned size of the launch
+  int launch_workgroups = 0;                 // 0 = workgroups; else a smaller size asked for by the caller
   unsigned run_parity = 0;                   // control block the next run uses
   int64_t runs = 0;
   uint32_t run_number = 0;                   // number of the most recent run (per-item completion flags hold it)
@@ -330,7 +331,7 @@ static st_status chain_launch(st_chain* c, void* stream, uint64_t* prof_dev) {
   }
   ST_HIP((hipError_t)launch_chain(c->d_ops, c->d_items, (uint32_t)c->items.size(), c->d_colbegin, (uint32_t)c->n_queues, c->d_ctl[p],
                                   c->d_ctl[p ^ 1u], c->ctl_slots, c->d_item_flags, c->run_number, c->spin_limit_ticks, c->flags,
-                                  c->workgroups, stream, prof_dev));
+                                  c->launch_workgroups > 0 ? c->launch_workgroups : c->workgroups, stream, prof_dev));
   c->run_parity = p ^ 1u;
   ++c->runs;
   return ST_OK;
@@ -382,6 +383,13 @@ extern "C" st_status st_chain_set_wait_limit_us(st_chain* chain, int64_t microse
   if (!chain) return fail(ST_ERR_INVALID_ARG, "chain is NULL");
   if (microseconds < 0 || microseconds > 40000000) return fail(ST_ERR_INVALID_ARG, "limit must be between 0 and 40 s");
   chain->spin_limit_ticks = (uint32_t)(microseconds * 100);
+  return ST_OK;
+}
+
+extern "C" st_status st_chain_set_workgroups(st_chain* chain, int32_t workgroups) {
+  if (!chain) return fail(ST_ERR_INVALID_ARG, "chain is NULL");
+  if (workgroups < 0 || workgroups > chain->workgroups) return fail(ST_ERR_INVALID_ARG, "workgroups must be between 0 and %d", chain->workgroups);
+  chain->launch_workgroups = workgroups;
   return ST_OK;
 }
 

@@ -24,7 +24,7 @@ EXPORTS = ["st_conv_plan", "st_conv_run", "st_conv_run_noalloc", "st_conv_noallo
            "st_pipeline_create", "st_pipeline_slots", "st_pipeline_next", "st_pipeline_run", "st_pipeline_run_many", "st_pipeline_sync", "st_pipeline_destroy",
            "st_plan_cache_create", "st_plan_cache_get", "st_plan_cache_get_stats", "st_plan_cache_destroy", "st_conv_plan_info", "st_conv_plan_tenant_info", "st_conv_plan_worklist",
            "st_conv_plan_destroy", "st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
-           "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns", "st_chain_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
+           "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns", "st_chain_set_workgroups", "st_chain_destroy", "st_tile_shape", "st_tile_count", "st_maxpool_nhwc",
            "st_launch_empty", "st_launch_copy", "st_status_string", "st_last_error_message"]
 
 
@@ -157,6 +157,7 @@ def lib() -> ctypes.CDLL:
         L.st_chain_run_profiled.argtypes = [vp, vp, P(ctypes.c_uint64), i64]
         L.st_chain_aborted.argtypes = [vp, P(i32)]
         L.st_chain_set_wait_limit_us.argtypes = [vp, i64]
+        L.st_chain_set_workgroups.argtypes = [vp, i32]
         L.st_chain_get_info.argtypes = [vp, P(st_chain_info)]
         L.st_chain_get_op_info.argtypes = [vp, i32, P(st_chain_op_info)]
         L.st_chain_worklist.argtypes = [vp, P(P(st_work_item)), P(i64)]
@@ -164,7 +165,7 @@ def lib() -> ctypes.CDLL:
         L.st_chain_destroy.argtypes = [vp]
         L.st_chain_destroy.restype = None
         for name in ("st_chain_plan", "st_chain_run", "st_chain_run_profiled", "st_chain_aborted", "st_chain_set_wait_limit_us",
-                     "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns"):
+                     "st_chain_get_info", "st_chain_get_op_info", "st_chain_worklist", "st_chain_columns", "st_chain_set_workgroups"):
             getattr(L, name).restype = i32
         L.st_tile_shape.argtypes = [i32, P(i32), P(i32), P(i32)]
         L.st_tile_count.argtypes = []
@@ -475,6 +476,9 @@ class Chain:
         if n.value == 0:
             return np.zeros(0, dtype=WORK_ITEM_DTYPE)
         return np.frombuffer(ctypes.string_at(p, n.value * ctypes.sizeof(st_work_item)), dtype=WORK_ITEM_DTYPE).copy()
+
+    def set_workgroups(self, n: int) -> None:
+        _check(lib().st_chain_set_workgroups(self.handle, int(n)), "st_chain_set_workgroups")
 
     def columns(self) -> np.ndarray:
         """Column boundaries (8 * 2 * info().columns + 1 entries; empty with one queue), see st_chain_columns."""

@@ -116,6 +116,12 @@ def test_resnet_chain_queue_and_thresholds():
         chain.run()
     assert e.value.status == sc.ST_ERR_UNSUPPORTED
     assert chain.aborted() is False
+    chain.set_workgroups(info.workgroups)
+    chain.set_workgroups(0)
+    for bad in (-1, info.workgroups + 1):
+        with pytest.raises(sc.StError) as e:
+            chain.set_workgroups(bad)
+        assert e.value.status == sc.ST_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("chain_queues,want", [(0, 8), (1, 1), (2, 8)])

@@ -218,3 +218,48 @@ def test_chain_sixteen_sequences_on_pingpong_buffers():
             for q, (_, _, a, b, _) in enumerate(seqs):
                 assert torch.equal(a, want[q][0]) and torch.equal(b, want[q][1]), f"pass {rep}, sequence {q}"
     assert not chain.aborted()
+
+
+@pytest.mark.parametrize("chain_queues", [0, 1])
+def test_chain_with_fewer_workgroups_than_planned(chain_queues):
+    """The one-queue form completes with any number of workgroups.  The column form needs a workgroup for every column
+    in use: launched with one workgroup per compute unit only (nobody draws the shared columns), the dependants of the
+    undone entries give up after the wait limit, the kernel exits by itself, the pass is reported as abandoned, and
+    the next full-size pass is right again."""
+    import torch
+    from paper_1901_00041_amd.stack import ResNetStack
+    stack = ResNetStack(n_tenants=8)
+    last = stack.steps[-1]
+    stack.run("fused")
+    torch.cuda.synchronize()
+    want = stack.buf[last.dst].clone()
+    stack.build_chain(chain_queues)
+    chain = stack.chain
+    planned = chain.info().workgroups
+    with pytest.raises(sc.StError):
+        chain.set_workgroups(planned + 1)
+
+    def scrub():
+        for i, b in stack.buf.items():
+            if i != 0:
+                b.zero_()
+
+    scrub()
+    if chain_queues == 1:
+        chain.set_workgroups(64)
+        stack.run("fused_chain")
+        torch.cuda.synchronize()
+        assert not chain.aborted() and torch.equal(stack.buf[last.dst], want)
+    else:
+        assert planned == 512
+        chain.set_workgroups(256)
+        chain.set_wait_limit_us(2000)
+        stack.run("fused_chain")
+        torch.cuda.synchronize()
+        assert chain.aborted()
+        chain.set_workgroups(0)
+        chain.set_wait_limit_us(100000)
+        scrub()
+        stack.run("fused_chain")
+        torch.cuda.synchronize()
+        assert not chain.aborted() and torch.equal(stack.buf[last.dst], want)
