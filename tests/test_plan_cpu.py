@@ -418,3 +418,21 @@ def test_pipeline_share_table_and_argument_checks():
         assert st == sc.ST_ERR_DEVICE and not out.value and sc.lib().st_last_error_message()
     assert sc.lib().st_pipeline_sync(None) == sc.ST_ERR_INVALID_ARG
     assert sc.lib().st_pipeline_run(None, None) == sc.ST_ERR_INVALID_ARG
+
+
+def test_default_plan_prefers_one_workgroup_per_compute_unit_when_the_model_says_so():
+    """With the default slot target the planner also plans for 256 slots (one workgroup per compute unit, each 1.3x faster
+    than beside a second one) and takes that plan when its modelled launch is shorter: config 3 (8 tenants of 3x3
+    256->256 @14x14) becomes 224 tiles of 64x64 instead of 416 of 32x64; an explicit target keeps the caller's choice;
+    config 4 (more than a thousand tiles either way) is unaffected."""
+    shapes = synth.config_shapes(3)
+    auto = sc.st_conv_plan([_desc(s) for s in shapes], sc.plan_opts(host_only=1))
+    forced = sc.st_conv_plan([_desc(s) for s in shapes], sc.plan_opts(host_only=1, target_items=400))
+    ia, ifo = sc.st_conv_plan_info(auto), sc.st_conv_plan_info(forced)
+    assert ia.n_items <= 256 < ifo.n_items
+    assert {(sc.st_conv_plan_tenant_info(auto, t).MT, sc.st_conv_plan_tenant_info(auto, t).NT) for t in range(len(shapes))} == {(64, 64)}
+    assert {(sc.st_conv_plan_tenant_info(forced, t).MT, sc.st_conv_plan_tenant_info(forced, t).NT) for t in range(len(shapes))} == {(32, 64)}
+    shapes4 = synth.config_shapes(4)
+    a4 = sc.st_conv_plan_info(sc.st_conv_plan([_desc(s) for s in shapes4], sc.plan_opts(host_only=1)))
+    f4 = sc.st_conv_plan_info(sc.st_conv_plan([_desc(s) for s in shapes4], sc.plan_opts(host_only=1, target_items=400)))
+    assert a4.n_items == f4.n_items > 256
