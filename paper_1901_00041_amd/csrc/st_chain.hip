@@ -192,6 +192,9 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
       ConstOp& T = *(ConstOp*)(a.ops + it.tenant);
       uint64_t* prof = a.prof ? a.prof + (size_t)idx * kProfSlots : nullptr;
       uint64_t waited = 0;
+      // one word of every 64-byte line of the op record, requested before the dependency wait and used after it, so
+      // that the record sits in the scalar cache when the tile code reads its fields
+      const uint32_t rec_touch = (uint32_t)(uintptr_t)T.x ^ (uint32_t)T.R ^ (uint32_t)T.tiles_m ^ T.x_bytes ^ T.chain_flag_base;
       if (T.chain_need != 0u) {
         // Wavefront 0 looks at the dependency: with flags, at those of the sequence's previous stage, 64 at a time from
         // the first that was not yet set (they were stored by workgroups of this XCD and sit, newer than memory, in
@@ -254,6 +257,7 @@ __global__ __launch_bounds__(kThreads, 2) void st_chain_kernel(const ChainArgs a
           if (s_msg[1] == 0u) break;
         }
       }
+      asm volatile("" ::"s"(rec_touch));
       if (T.cfg == kChainPoolCfg && prof && tid == 0) prof[4] = wall_clock64();
       chain_item(T, it, smem, prof);
       // Completion.  Outputs were stored write-through; channel counts that are not a multiple of 8 take an epilogue
