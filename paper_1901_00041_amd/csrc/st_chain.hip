@@ -47,8 +47,8 @@ struct ChainArgs {
   const uint32_t* colbegin;   // columns: column j of XCD x is items[colbegin[x * 2 * kChainColumns + j] .. colbegin[.. + j + 1])
 };
 
-constexpr int kChainGraceLooks = 12;             // looks at a dependency (0.3 us each) before the filter touches are issued
-                                                 // (measured per pass of the 8 x 53-layer chain: 3 looks 495 us, 6: 487, 12: 482, 30: 484, never touching: 494)
+constexpr int kChainGraceLooks = 24;             // looks at a dependency (0.3 us each) before the filter touches are issued
+                                                 // (per pass of the 8 x 53-layer chain: 6 looks 459 us, 12: 456, 24 and 48: 454, never touching: 456)
 constexpr uint32_t kChainMaxPolls = 1u << 22;   // a poll takes a microsecond or so: seconds, far beyond any real wait
 
 // The op table and the queue never change while a launch runs: they are read through the constant address space, so
